@@ -1,0 +1,16 @@
+"""Fused multi-head attention forward for MI355X (gfx950), behind a C-ABI library.
+
+`attn_fwd`, `attn_supported`, `attn_status_str` mirror the entry points of
+``include/attn.h``; they are loaded lazily so that the input generator can be
+imported on a machine without the HIP library.
+"""
+from . import inputs  # noqa: F401
+
+__all__ = ["inputs", "attn_fwd", "attn_supported", "attn_status_str", "lib"]
+
+
+def __getattr__(name):
+    if name in ("attn_fwd", "attn_supported", "attn_status_str", "lib", "AttnError"):
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(name)
