@@ -1,0 +1,114 @@
+"""Thin Python binding of the C-ABI library (include/attn.h): argument marshalling only.
+
+PyTorch supplies device memory and the stream; every step of the attention path runs inside
+the HIP kernel.  There is no CPU or PyTorch fallback: if the shared library is missing the
+import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+F16 = 0
+BF16 = 1
+
+
+class AttnError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"attn_fwd failed with status {status}: {msg}")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_build.LIB):
+        try:
+            _build.build_lib()
+        except Exception as e:  # no compiler, or the build failed: there is nothing to fall back to
+            raise ImportError(f"{_build.LIB} is missing and could not be built: {e}") from e
+    lib = ctypes.CDLL(_build.LIB)
+    vp = ctypes.c_void_p
+    lib.attn_fwd.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int, vp]
+    lib.attn_fwd.restype = ctypes.c_int
+    lib.attn_supported.argtypes = [ctypes.c_int] * 4
+    lib.attn_supported.restype = ctypes.c_int
+    lib.attn_status_str.argtypes = [ctypes.c_int]
+    lib.attn_status_str.restype = ctypes.c_char_p
+    lib.attn_kernel_name.argtypes = [ctypes.c_int] * 4
+    lib.attn_kernel_name.restype = ctypes.c_char_p
+    for f in (lib.attn_tile_rows, lib.attn_tile_keys):
+        f.argtypes = [ctypes.c_int] * 3
+        f.restype = ctypes.c_int
+    return lib
+
+
+lib = _load()
+
+
+def attn_status_str(status: int) -> str:
+    return lib.attn_status_str(int(status)).decode()
+
+
+def attn_supported(S: int, D: int, dtype: int, causal: bool) -> bool:
+    return bool(lib.attn_supported(int(S), int(D), int(dtype), int(bool(causal))))
+
+
+def attn_kernel_name(S: int, D: int, dtype: int, causal: bool):
+    n = lib.attn_kernel_name(int(S), int(D), int(dtype), int(bool(causal)))
+    return n.decode() if n else None
+
+
+def attn_tile_rows(D: int, dtype: int, causal: bool) -> int:
+    return int(lib.attn_tile_rows(int(D), int(dtype), int(bool(causal))))
+
+
+def attn_tile_keys(D: int, dtype: int, causal: bool) -> int:
+    return int(lib.attn_tile_keys(int(D), int(dtype), int(bool(causal))))
+
+
+def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale, dtype, stream) -> int:
+    """The C entry point as is: device addresses as ints (0 = NULL), returns the status."""
+    return int(lib.attn_fwd(q_ptr or None, k_ptr or None, v_ptr or None, o_ptr or None, lse_ptr or None,
+                            int(B), int(H), int(S), int(D), int(causal), float(scale), int(dtype),
+                            stream or None))
+
+
+def attn_fwd(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None, want_lse: bool = True):
+    """attn_fwd on torch device tensors.
+
+    q, k, v : [B,H,S,D] contiguous torch.float16 or torch.bfloat16 tensors on the GPU.
+    o, lse  : optional preallocated fp32 outputs ([B,H,S,D], [B,H,S]); allocated if None.
+    stream  : a torch.cuda.Stream (default: the current stream).
+    Returns (o, lse).  Asynchronous, like the C call.
+    """
+    import torch
+
+    if q.dtype == torch.float16:
+        dtype = F16
+    elif q.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("q, k, v must be float16 or bfloat16")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share one dtype")
+    if q.dim() != 4 or k.shape != q.shape or v.shape != q.shape:
+        raise ValueError("q, k, v must be [B,H,S,D] of one shape")
+    for t in (q, k, v):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("q, k, v must be contiguous device tensors")
+    B, H, S, D = q.shape
+    if o is None:
+        o = torch.empty((B, H, S, D), dtype=torch.float32, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty((B, H, S), dtype=torch.float32, device=q.device)
+    for t, shp in ((o, (B, H, S, D)), (lse, (B, H, S))):
+        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != shp or not t.is_contiguous()
+                              or not t.is_cuda):
+            raise ValueError("o / lse must be contiguous fp32 device tensors of shape [B,H,S,D] / [B,H,S]")
+    st = (stream or torch.cuda.current_stream(q.device)).cuda_stream
+    rc = attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                      lse.data_ptr() if lse is not None else 0, B, H, S, D, causal, scale, dtype, st)
+    if rc != 0:
+        raise AttnError(rc, attn_status_str(rc))
+    return o, lse

@@ -1,0 +1,71 @@
+// C-ABI layer of the gfx950 attention forward: argument validation (no HIP call before every
+// check has passed), then one asynchronous kernel launch on the caller's stream.
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+
+#include "../../include/attn.h"
+#include "attn_launch.h"
+
+namespace {
+bool d_supported(int D) { return D == 64 || D == 128; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+}  // namespace
+
+extern "C" int attn_supported(int S, int D, int dtype, int causal) {
+    (void)causal;
+    return (S >= 1 && d_supported(D) && (dtype == ATTN_F16 || dtype == ATTN_BF16)) ? 1 : 0;
+}
+
+extern "C" const char* attn_status_str(int status) {
+    switch (status) {
+        case ATTN_OK: return "ok";
+        case ATTN_ERR_NULL: return "q, k, v or o is a null pointer";
+        case ATTN_ERR_SHAPE: return "B, H, S and D must be positive (and a tensor at most 2^40 elements)";
+        case ATTN_ERR_DTYPE: return "dtype must be ATTN_F16 (0) or ATTN_BF16 (1)";
+        case ATTN_ERR_SCALE: return "scale must be finite";
+        case ATTN_ERR_UNSUPPORTED: return "no kernel instance for this head dimension (D must be 64 or 128)";
+        case ATTN_ERR_ALIGN: return "every pointer must be 16-byte aligned";
+        case ATTN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+        default: return "unknown status";
+    }
+}
+
+extern "C" const char* attn_kernel_name(int S, int D, int dtype, int causal) {
+    if (!attn_supported(S, D, dtype, causal)) return nullptr;
+    static char names[2][2][2][64];
+    char* n = names[dtype][D == 128][causal != 0];
+    if (n[0] == 0)
+        std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d>", dtype, D, causal ? "true" : "false", ATTN_NW);
+    return n;
+}
+
+extern "C" int attn_tile_rows(int D, int dtype, int causal) {
+    return attn_supported(1, D, dtype, causal) ? ATTN_NW * 32 : 0;
+}
+
+extern "C" int attn_tile_keys(int D, int dtype, int causal) {
+    return attn_supported(1, D, dtype, causal) ? ATTN_BC : 0;
+}
+
+extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int B, int H, int S, int D,
+                        int causal, float scale, int dtype, void* stream) {
+    if (!q || !k || !v || !o) return ATTN_ERR_NULL;
+    if (B <= 0 || H <= 0 || S <= 0 || D <= 0) return ATTN_ERR_SHAPE;
+    const long long bh = (long long)B * H;
+    if (bh > 0x7fffffffLL || (double)bh * S * D > 1099511627776.0) return ATTN_ERR_SHAPE;
+    if (dtype != ATTN_F16 && dtype != ATTN_BF16) return ATTN_ERR_DTYPE;
+    if (!std::isfinite(scale)) return ATTN_ERR_SCALE;
+    if (!d_supported(D)) return ATTN_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return ATTN_ERR_ALIGN;
+
+    AttnLaunch a;
+    a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+    a.BH = (int)bh; a.S = S; a.D = D;
+    a.causal = causal != 0;
+    a.dtype = dtype;
+    a.c = std::fabs(scale) * 1.4426950408889634f;
+    a.qsign = std::signbit(scale) && scale != 0.f ? 0x80008000u : 0u;
+    a.stream = stream;
+    return attn_launch(a) == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+}

@@ -1,0 +1,306 @@
+// Fused multi-head attention forward for gfx950 (MI355X): O = softmax(Q K^T * scale [+ causal]) V
+// and the per-row logsumexp, one pass over K/V with a running (online) softmax.
+//
+// The operation is the "flash-attention" kernel class of the paper's Table 2; the paper's
+// subject is the order of memory and compute instructions inside such a fixed kernel
+// (Sections 2.4, 3.5).  Here that order is set by hand for CDNA4.
+//
+// Work split
+//   workgroup = NW wavefronts, each owning 32 consecutive query rows of one (b,h);
+//   K/V stream through LDS in tiles of BC = 64 keys shared by the whole workgroup.
+//
+// Register layout (64-wide wavefront, lane l, half h = l/32, l32 = l%32)
+//   Everything is computed transposed so that one lane only ever holds values of ONE query row:
+//     S^T (keys x queries) = K_tile . Q^T      v_mfma_f32_32x32x16: A = K rows, B = Q^T
+//       accumulator register r of key block jb holds  S[q = l32][key = 32 jb + 8 (r/4) + 4 h + r%4]
+//     O^T (d x queries)  += V_tile^T . P^T     A = V^T (LDS transpose read), B = P^T
+//       The B operand of key step (jb,t) is registers 8t..8t+7 of block jb as they are; the
+//       contraction index is therefore visited in the permuted order
+//         key(slot e of half h) = 32 jb + 16 t + 8 (e/4) + 4 h + e%4,
+//       and the V^T operand is fetched in that same order, so P never leaves registers.
+//   Row maximum and row sum are an in-lane reduction plus one exchange between the halves.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "attn_launch.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define LDS_AS __attribute__((address_space(3)))
+
+template <int DT> struct Elem;
+template <> struct Elem<0> {  // IEEE binary16
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // round to nearest even
+        f32x2 x = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
+    }
+};
+template <> struct Elem<1> {  // bfloat16
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // round to nearest even
+        f32x2 x = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+    }
+};
+
+// 4 x 16-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
+// the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4 of its group.
+__device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t* p) {
+    s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)p);
+    return __builtin_bit_cast(u32x2, t);
+}
+
+// value held by the other half of the wavefront (lane l <-> lane l^32)
+__device__ __forceinline__ float other_half(float x) {
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    // lanes <32 get (own, upper's); lanes >=32 get (lower's, own)
+    return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+template <int DT, int D, bool CAUSAL, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                           const uint16_t* __restrict__ v, float* __restrict__ o,
+                                                           float* __restrict__ lse, int S, int BH, int nqt, float c,
+                                                           uint32_t qsign) {
+    using E = Elem<DT>;
+    constexpr int NT = NW * 64;        // threads
+    constexpr int BR = NW * 32;        // query rows per workgroup
+    constexpr int BC = 64;             // keys per tile
+    constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
+    constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
+    constexpr int KSTR = D + 8;        // LDS row stride of K in elements (16 B pad: b128 reads of 16 rows hit 64 banks once)
+    constexpr int VSTR = D + 32;       // LDS row stride of V (64 B pad: 4 rows x 64 B of a transpose read tile the banks)
+    constexpr int CPR = D / 8;         // 16-byte chunks per row
+    constexpr int CH = BC * CPR / NT;  // chunks each thread stages per tensor per tile
+    static_assert(BC * CPR % NT == 0, "tile must split evenly over the threads");
+
+    __shared__ __attribute__((aligned(16))) uint16_t k_lds[BC * KSTR];
+    __shared__ __attribute__((aligned(16))) uint16_t v_lds[BC * VSTR];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int h = lane >> 5;
+
+    // heaviest query tiles first (under the causal mask tile t reads t+1 key tiles)
+    const int bh = blockIdx.x % BH;
+    const int qt = CAUSAL ? nqt - 1 - blockIdx.x / BH : blockIdx.x / BH;
+    const int q0 = qt * BR;
+    const int qw0 = q0 + 32 * wave;          // first query row of this wavefront
+    const int qrow = qw0 + l32;              // this lane's query row (may lie beyond S on the last tile)
+    const int qrow_ld = qrow < S ? qrow : S - 1;
+
+    const size_t head = (size_t)bh * S * D;
+    const uint16_t* qh = q + head;
+    const uint16_t* kh = k + head;
+    const uint16_t* vh = v + head;
+
+    // Q^T operand, resident for the whole kernel: lane holds q[qrow][16 ks + 8 h .. +7]
+    u32x4 qf[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        qf[ks] = *(const u32x4*)(qh + (size_t)qrow_ld * D + 16 * ks + 8 * h);
+        qf[ks] ^= qsign;   // a negative scale is folded into the sign of q (exact)
+    }
+
+    const int kv_end = CAUSAL ? (q0 + BR < S ? q0 + BR : S) : S;
+    const int ntiles = (kv_end + BC - 1) / BC;
+
+    u32x4 kreg[CH], vreg[CH];
+    auto load_tile = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int idx = tid + i * NT;
+            const int row = idx / CPR, col = idx % CPR;
+            int grow = j0 + row;
+            grow = grow < S ? grow : S - 1;     // rows past the end are masked later; keep the address valid
+            kreg[i] = *(const u32x4*)(kh + (size_t)grow * D + col * 8);
+            vreg[i] = *(const u32x4*)(vh + (size_t)grow * D + col * 8);
+        }
+    };
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int idx = tid + i * NT;
+            const int row = idx / CPR, col = idx % CPR;
+            *(u32x4*)(k_lds + row * KSTR + col * 8) = kreg[i];
+            *(u32x4*)(v_lds + row * VSTR + col * 8) = vreg[i];
+        }
+    };
+
+    f32x16 acc_o[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+    float m_run = -INFINITY;   // running row maximum of the scaled logits, base-2 units
+    float l_run = 0.f;         // this lane's share of the running row sum
+
+    // per-lane LDS offsets
+    const int k_off = l32 * KSTR + 8 * h;
+    const int v_off = (4 * h + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+    load_tile(0);
+    for (int t = 0; t < ntiles; ++t) {
+        const int j0 = t * BC;
+        __syncthreads();   // everyone is done reading the previous tile
+        store_tile();
+        __syncthreads();
+        if (t + 1 < ntiles) load_tile(j0 + BC);   // in flight while this tile is computed
+
+        if (CAUSAL && j0 > qw0 + 31) continue;    // every key of the tile is masked for this wavefront
+
+        // ---- S^T = K . Q^T ----
+        f32x16 s[2];
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                u32x4 a = *(const u32x4*)(k_lds + k_off + 32 * jb * KSTR + 16 * ks);
+                s[jb] = E::mfma(a, qf[ks], s[jb]);
+            }
+
+        // ---- mask, running maximum ----
+        const bool need_mask = (j0 + BC > S) || (CAUSAL && j0 + BC - 1 > qw0);
+        float m_new;
+        if (need_mask) {
+            // scale first, then mask, so that scale == 0 cannot meet an infinity
+            const int lim = (CAUSAL ? qrow_ld : S - 1) - j0 - 4 * h;
+            float mx = -INFINITY;
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int off = 32 * jb + 8 * (r / 4) + (r % 4);
+                    float x = s[jb][r] * c;
+                    x = off > lim ? -INFINITY : x;
+                    s[jb][r] = x;
+                    mx = fmaxf(mx, x);
+                }
+            mx = fmaxf(mx, other_half(mx));
+            m_new = fmaxf(m_run, mx);
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[jb][r] = __builtin_amdgcn_exp2f(s[jb][r] - m_new);
+        } else {
+            float mx = s[0][0];
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[jb][r]);
+            mx = fmaxf(mx, other_half(mx));
+            m_new = fmaxf(m_run, mx * c);    // c >= 0
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[jb][r] = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -m_new));
+        }
+
+        // ---- running sum, rescale ----
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) psum += s[jb][r];
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+
+        // ---- P^T operands: registers 8t..8t+7 of block jb, rounded to the input type ----
+        u32x4 pf[2][2];
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pf[jb][tt][e] = E::pack2(s[jb][8 * tt + 2 * e], s[jb][8 * tt + 2 * e + 1]);
+
+        // ---- O^T += V^T . P^T ----
+#pragma unroll
+        for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int i = 0; i < DB; ++i) {
+                    const uint16_t* p = v_lds + v_off + (32 * jb + 16 * tt) * VSTR + 32 * i;
+                    u32x2 lo = lds_read_tr16(p);
+                    u32x2 hi = lds_read_tr16(p + 8 * VSTR);
+                    u32x4 a = {lo[0], lo[1], hi[0], hi[1]};
+                    acc_o[i] = E::mfma(a, pf[jb][tt], acc_o[i]);
+                }
+    }
+
+    // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
+    const float l_tot = l_run + other_half(l_run);
+    const float inv = 1.0f / l_tot;
+    if (qrow < S) {
+        float* orow = o + head + (size_t)qrow * D;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 x = {acc_o[i][4 * g] * inv, acc_o[i][4 * g + 1] * inv, acc_o[i][4 * g + 2] * inv,
+                           acc_o[i][4 * g + 3] * inv};
+                *(f32x4*)(orow + 32 * i + 8 * g + 4 * h) = x;
+            }
+        if (lse != nullptr && h == 0)
+            lse[(size_t)bh * S + qrow] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    }
+}
+
+template <int DT, int D, bool CAUSAL, int NW>
+hipError_t launch(const AttnLaunch& a) {
+    constexpr int BR = NW * 32;
+    const int nqt = (a.S + BR - 1) / BR;
+    const long long blocks = (long long)nqt * a.BH;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((attn_fwd_kernel<DT, D, CAUSAL, NW>), dim3((unsigned)blocks), dim3(NW * 64), 0, (hipStream_t)a.stream,
+                       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.o, a.lse, a.S, a.BH, nqt, a.c,
+                       a.qsign);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// dispatch on (dtype, D, causal); arguments were validated by the caller
+hipError_t attn_launch(const AttnLaunch& a) {
+#define ATTN_CASE(DT, DD, CZ)                                       \
+    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW>(a);
+    ATTN_CASE(0, 64, false)
+    ATTN_CASE(0, 64, true)
+    ATTN_CASE(0, 128, false)
+    ATTN_CASE(0, 128, true)
+    ATTN_CASE(1, 64, false)
+    ATTN_CASE(1, 64, true)
+    ATTN_CASE(1, 128, false)
+    ATTN_CASE(1, 128, true)
+#undef ATTN_CASE
+    return hipErrorInvalidValue;
+}

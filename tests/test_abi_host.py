@@ -1,0 +1,80 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments before any HIP call (so these run on a machine without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2501_08071_amd as pkg
+    pkg.lib  # force the load
+    return pkg
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(P):
+    names = declared_symbols()
+    assert {"attn_fwd", "attn_supported", "attn_status_str"} <= set(names)
+    for n in names:
+        assert hasattr(P.lib, n), f"{n} is declared in attn.h but not exported"
+
+
+def test_status_strings(P):
+    seen = set()
+    for st in range(0, -8, -1):
+        s = P.attn_status_str(st)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert P.attn_status_str(-99) == "unknown status"
+
+
+def test_supported_matrix(P):
+    for D in (64, 128):
+        for dt in (0, 1):
+            for causal in (False, True):
+                assert P.attn_supported(1, D, dt, causal) and P.attn_supported(16384, D, dt, causal)
+                assert P.attn_kernel_name(128, D, dt, causal)
+                assert P.attn_tile_rows(D, dt, causal) % 32 == 0 and P.attn_tile_keys(D, dt, causal) > 0
+    assert not P.attn_supported(128, 32, 0, False)
+    assert not P.attn_supported(128, 64, 2, False)
+    assert not P.attn_supported(0, 64, 0, False)
+    assert P.attn_kernel_name(128, 96, 0, False) is None
+
+
+def test_bad_arguments_rejected_without_a_gpu(P):
+    ok = 4096  # any non-null 16-byte aligned address: validation fails before it is touched
+    f = P.attn_fwd_raw
+    assert f(0, ok, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1
+    assert f(ok, 0, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1
+    assert f(ok, ok, 0, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1
+    assert f(ok, ok, ok, 0, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1
+    assert f(ok, ok, ok, ok, ok, 0, 1, 8, 64, 0, 1.0, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, 1, -1, 8, 64, 0, 1.0, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, 1, 1, 0, 64, 0, 1.0, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, 1, 1, 8, 0, 0, 1.0, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, 1 << 20, 1 << 20, 8, 64, 0, 1.0, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 2, 0) == -3
+    assert f(ok, ok, ok, ok, ok, 1, 1, 8, 64, 0, float("nan"), 0, 0) == -4
+    assert f(ok, ok, ok, ok, ok, 1, 1, 8, 64, 0, float("inf"), 0, 0) == -4
+    assert f(ok, ok, ok, ok, ok, 1, 1, 8, 96, 0, 1.0, 0, 0) == -5
+    assert f(ok + 8, ok, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -6
+
+
+def test_library_links_only_the_hip_runtime():
+    """No torch types cross the boundary: the library must not depend on libtorch."""
+    import subprocess
+    lib = os.path.join(ROOT, "paper_2501_08071_amd", "libattn_gfx950.so")
+    out = subprocess.run(["ldd", lib], capture_output=True, text=True).stdout
+    assert "torch" not in out and "libc10" not in out
+    assert "amdhip64" in out

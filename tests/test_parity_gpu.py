@@ -1,0 +1,150 @@
+"""GPU parity: the HIP attention forward, called through the C ABI, against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2501_08071_amd as P
+from paper_2501_08071_amd import inputs as I
+from parity import (MAX_ABS, assert_parity, check_full, edge_rows, errors, run_gpu, to_device)
+
+pytestmark = pytest.mark.gpu
+F16, BF16 = I.F16, I.BF16
+
+
+# ---- small shapes, every output element compared ---------------------------------------
+
+SMALL = [
+    # B, H, S, D  -- S chosen to hit: one key, sub-tile, tile edges +-1, several query tiles, ragged tails
+    (2, 2, 1, 64), (1, 2, 2, 128), (1, 3, 31, 64), (1, 2, 33, 128), (2, 1, 64, 64), (1, 2, 65, 128),
+    (1, 2, 127, 64), (1, 1, 128, 128), (1, 2, 129, 64), (2, 2, 200, 128), (1, 3, 257, 64), (1, 2, 300, 128),
+    (2, 2, 517, 64), (1, 2, 640, 128),
+]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("B,H,S,D", SMALL)
+def test_small_shapes_full_compare(B, H, S, D, dtype, causal):
+    q, k, v = I.gen_tensors(B, H, S, D, dtype, workload_id=100 + S)
+    check_full(q, k, v, dtype, causal, 1 / math.sqrt(D), f"B{B} H{H} S{S} D{D} dt{dtype} causal{causal}")
+
+
+def test_workload_1_full():
+    w = I.workload(1)
+    q, k, v = I.gen_inputs(w)
+    mx, mean, lrel = check_full(q, k, v, w.dtype, w.causal, w.scale, w.name)
+    print(f"{w.name}: max-abs {mx:.2e} mean-abs {mean:.2e} lse-rel {lrel:.2e}")
+
+
+@pytest.mark.parametrize("scale", [0.0, -0.125, 1.0, 1e-4])
+@pytest.mark.parametrize("causal", [False, True])
+def test_scale_values(scale, causal):
+    q, k, v = I.gen_tensors(1, 2, 200, 64, F16, workload_id=201)
+    check_full(q, k, v, F16, causal, scale, f"scale {scale}")
+
+
+def test_peaky_logits_small():
+    w = I.workload(5)
+    q, k, v = I.gen_tensors(2, 2, 384, w.D, w.dtype, workload_id=w.id, qk_mul=w.qk_mul, v_dist=w.v_dist)
+    check_full(q, k, v, w.dtype, False, w.scale, "peaky small")
+    check_full(q, k, v, w.dtype, True, w.scale, "peaky small causal")
+
+
+def test_huge_logits_do_not_overflow():
+    """|s| up to ~1e4: exp would overflow without the running maximum."""
+    q, k, v = I.gen_tensors(1, 2, 256, 64, BF16, workload_id=202, qk_mul=32.0)
+    check_full(q, k, v, BF16, False, 1.0, "huge logits")
+
+
+def test_closed_forms_on_gpu():
+    S, D = 300, 64
+    q, k, v = I.gen_tensors(1, 2, S, D, F16, workload_id=203)
+    V = I.bits_to_f64(v, F16)
+    # zero queries: running mean of V, lse = ln(i+1)
+    o, lse = run_gpu(np.zeros_like(q), k, v, F16, True, 0.125)
+    want = np.cumsum(V, 2) / np.arange(1, S + 1)[None, None, :, None]
+    assert np.abs(o - want).max() < 2e-3
+    assert np.abs(lse - np.log(np.arange(1, S + 1))).max() < 1e-4
+    # constant V comes back unchanged
+    cv = I.to_bits(np.full((1, 2, S, D), 0.75, np.float32), F16)
+    o, _ = run_gpu(q, k, cv, F16, False, 0.125)
+    assert np.abs(o - 0.75).max() < 1e-3
+    # causal first row equals V[0]
+    o, lse = run_gpu(q, k, v, F16, True, 0.125)
+    assert np.abs(o[:, :, 0] - V[:, :, 0]).max() < 1e-6
+
+
+def test_lse_optional_and_outputs_reused():
+    q, k, v = I.gen_tensors(1, 2, 130, 64, F16, workload_id=204)
+    o1, lse1 = run_gpu(q, k, v, F16, True, 0.125)
+    o2, none = run_gpu(q, k, v, F16, True, 0.125, want_lse=False)
+    assert none is None and np.array_equal(o1, o2)
+
+
+def test_run_to_run_bitwise_determinism():
+    w = I.workload(2)
+    q, k, v = I.gen_tensors(2, 4, 1024, w.D, w.dtype, workload_id=w.id)
+    dq, dk, dv = (to_device(t, w.dtype) for t in (q, k, v))
+    o0, l0 = P.attn_fwd(dq, dk, dv, True, w.scale)
+    for _ in range(5):
+        o1, l1 = P.attn_fwd(dq, dk, dv, True, w.scale)
+        assert torch.equal(o0, o1) and torch.equal(l0, l1)
+
+
+def test_non_default_stream_and_guard_bytes():
+    """Runs on a side stream and writes nothing outside o / lse."""
+    B, H, S, D = 1, 2, 100, 64
+    q, k, v = I.gen_tensors(B, H, S, D, BF16, workload_id=205)
+    dq, dk, dv = (to_device(t, BF16) for t in (q, k, v))
+    pad = 1024
+    obuf = torch.full((B * H * S * D + 2 * pad,), 7.0, device="cuda")
+    lbuf = torch.full((B * H * S + 2 * pad,), 7.0, device="cuda")
+    o = obuf[pad:-pad].view(B, H, S, D)
+    lse = lbuf[pad:-pad].view(B, H, S)
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        P.attn_fwd(dq, dk, dv, True, 0.125, o=o, lse=lse, stream=st)
+    st.synchronize()
+    assert (obuf[:pad] == 7).all() and (obuf[-pad:] == 7).all()
+    assert (lbuf[:pad] == 7).all() and (lbuf[-pad:] == 7).all()
+    o_ref, l_ref = oracle.attn_oracle(q, k, v, True, 0.125, BF16)
+    assert_parity(o.cpu().numpy(), lse.cpu().numpy(), o_ref, l_ref, "side stream")
+
+
+# ---- the five workloads at full size, in the launch configuration the bench times -------
+
+@pytest.mark.parametrize("wid", [2, 3, 4, 5])
+def test_workloads_full_size_row_subset(wid):
+    """Every (b,h); rows at every tile edge +-1 plus a seeded random sample (rows are independent,
+    so the oracle on a row subset is exact for those rows)."""
+    w = I.workload(wid)
+    q, k, v = I.gen_inputs(w)
+    o, lse = run_gpu(q, k, v, w.dtype, w.causal, w.scale)
+    assert np.isfinite(o).all() and np.isfinite(lse).all()
+    br, bc = P.attn_tile_rows(w.D, w.dtype, w.causal), P.attn_tile_keys(w.D, w.dtype, w.causal)
+    # tile-edge rows for all tiles would be most of a 16k sequence: keep edges of the first and last 4 tiles
+    rows = edge_rows(w.S, br, bc, extra=w.S // 32, seed=wid)
+    if len(rows) > w.S // 8:
+        keep = (rows < 4 * br + 2) | (rows > w.S - 4 * br - 2)
+        rng = np.random.default_rng(wid)
+        rows = np.unique(np.concatenate([rows[keep], rng.choice(rows[~keep], w.S // 16, replace=False)]))
+    o_ref, lse_ref = oracle.attn_oracle(q, k, v, w.causal, w.scale, w.dtype, rows=rows)
+    mx, mean, lrel = assert_parity(o[:, :, rows], lse[:, :, rows], o_ref, lse_ref, w.name)
+    print(f"{w.name}: {len(rows)} rows/head: max-abs {mx:.2e} mean-abs {mean:.2e} lse-rel {lrel:.2e}")
+    # properties that hold at any size, over the whole output
+    V = I.bits_to_f64(v, w.dtype)
+    if not w.causal:
+        assert (o <= V.max(2, keepdims=True) + 1e-3).all() and (o >= V.min(2, keepdims=True) - 1e-3).all()
+    else:
+        assert np.abs(o[:, :, 0] - V[:, :, 0]).max() < 1e-6
+
+
+def test_workload_2_every_element():
+    w = I.workload(2)
+    q, k, v = I.gen_inputs(w)
+    mx, mean, lrel = check_full(q, k, v, w.dtype, w.causal, w.scale, w.name)
+    print(f"{w.name} full: max-abs {mx:.2e} mean-abs {mean:.2e} lse-rel {lrel:.2e}")
