@@ -9,6 +9,10 @@ from __future__ import annotations
 import ctypes
 import os
 
+# torch first: it carries its own copy of the HIP runtime (same soname as the system one), and the
+# process must end up with ONE runtime that owns both torch's streams and this library's kernels
+import torch
+
 from . import build as _build
 
 F16 = 0
@@ -82,8 +86,6 @@ def attn_fwd(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None,
     stream  : a torch.cuda.Stream (default: the current stream).
     Returns (o, lse).  Asynchronous, like the C call.
     """
-    import torch
-
     if q.dtype == torch.float16:
         dtype = F16
     elif q.dtype == torch.bfloat16:

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 
 #include "../../include/attn.h"
 #include "attn_launch.h"
@@ -67,5 +68,10 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, f
     a.c = std::fabs(scale) * 1.4426950408889634f;
     a.qsign = std::signbit(scale) && scale != 0.f ? 0x80008000u : 0u;
     a.stream = stream;
-    return attn_launch(a) == hipSuccess ? ATTN_OK : ATTN_ERR_LAUNCH;
+    const hipError_t err = attn_launch(a);
+    if (err != hipSuccess) {
+        if (std::getenv("ATTN_DEBUG")) std::fprintf(stderr, "attn_fwd: launch failed: %s\n", hipGetErrorString(err));
+        return ATTN_ERR_LAUNCH;
+    }
+    return ATTN_OK;
 }

@@ -281,10 +281,19 @@ hipError_t launch(const AttnLaunch& a) {
     const int nqt = (a.S + BR - 1) / BR;
     const long long blocks = (long long)nqt * a.BH;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((attn_fwd_kernel<DT, D, CAUSAL, NW>), dim3((unsigned)blocks), dim3(NW * 64), 0, (hipStream_t)a.stream,
-                       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, a.o, a.lse, a.S, a.BH, nqt, a.c,
-                       a.qsign);
-    return hipGetLastError();
+    const uint16_t* q = (const uint16_t*)a.q;
+    const uint16_t* k = (const uint16_t*)a.k;
+    const uint16_t* v = (const uint16_t*)a.v;
+    float* o = a.o;
+    float* lse = a.lse;
+    int S = a.S, BH = a.BH, nq = nqt;
+    float c = a.c;
+    uint32_t qsign = a.qsign;
+    void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign};
+    // the launch status is taken from the call itself: the thread's "last error" may hold a stale
+    // value left by an unrelated earlier runtime call of the host program
+    return hipLaunchKernel(reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>), dim3((unsigned)blocks),
+                           dim3(NW * 64), args, 0, (hipStream_t)a.stream);
 }
 
 }  // namespace
