@@ -9,6 +9,12 @@
 //   workgroup = NW wavefronts, each owning 32 consecutive query rows of one (b,h);
 //   K/V stream through LDS in tiles of BC = 64 keys shared by the whole workgroup.
 //
+// K/V movement
+//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), two buffers per tensor, the
+//   loads of tile t+1 issued right after the single barrier of tile t.  Such a load writes 1 KiB
+//   of consecutive LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an
+//   XOR swizzle of the 16-byte chunk index within each row, applied on the global-address side.
+//
 // Register layout (64-wide wavefront, lane l, half h = l/32, l32 = l%32)
 //   Everything is computed transposed so that one lane only ever holds values of ONE query row:
 //     S^T (keys x queries) = K_tile . Q^T      v_mfma_f32_32x32x16: A = K rows, B = Q^T
@@ -48,6 +54,9 @@ template <> struct Elem<0> {  // IEEE binary16
         f32x2 x = {lo, hi};
         return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
     }
+    static __device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {  // acc + p.lo + p.hi
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, p), f16x2{(_Float16)1.0f, (_Float16)1.0f}, acc, false);
+    }
 };
 template <> struct Elem<1> {  // bfloat16
     static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
@@ -57,11 +66,14 @@ template <> struct Elem<1> {  // bfloat16
         f32x2 x = {lo, hi};
         return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
     }
+    static __device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {  // acc + p.lo + p.hi
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p), bf16x2{(__bf16)1.0f, (__bf16)1.0f}, acc, false);
+    }
 };
 
 // 4 x 16-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
 // the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4 of its group.
-__device__ __forceinline__ u32x2 lds_read_tr16(const uint16_t* p) {
+__device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
     s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)p);
     return __builtin_bit_cast(u32x2, t);
 }
@@ -74,29 +86,42 @@ __device__ __forceinline__ float other_half(float x) {
     return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
 }
 
+// XOR swizzle of the 16-byte chunk index inside a K/V row in LDS (row = tile-local key index).
+// D=128 (16 chunks/row, a row spans all 64 banks): 16 consecutive rows must land on 16 different
+//   chunks (b128 reads of K) and 4 consecutive rows x 4 consecutive chunks likewise (transpose
+//   reads of V): swap the two low bit pairs of the row index.
+// D=64 (8 chunks/row, two rows span the banks): the same two conditions with the row parity
+//   already selecting the bank half: bit-reverse bits 1..3 of the row index.
+template <int D>
+__device__ __forceinline__ constexpr int swz(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))
+                    : ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1));
+}
+
+extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
 template <int DT, int D, bool CAUSAL, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WPE, ATTN_WPE))) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v, float* __restrict__ o,
                                                            float* __restrict__ lse, int S, int BH, int nqt, float c,
                                                            uint32_t qsign) {
     using E = Elem<DT>;
-    constexpr int NT = NW * 64;        // threads
     constexpr int BR = NW * 32;        // query rows per workgroup
-    constexpr int BC = 64;             // keys per tile
+    constexpr int BC = ATTN_BC;        // keys per tile
     constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
     constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
-    constexpr int KSTR = D + 8;        // LDS row stride of K in elements (16 B pad: b128 reads of 16 rows hit 64 banks once)
-    constexpr int VSTR = D + 32;       // LDS row stride of V (64 B pad: 4 rows x 64 B of a transpose read tile the banks)
+    constexpr int ROWB = 2 * D;        // bytes per K/V row
+    constexpr int TILEB = BC * ROWB;   // bytes per tile
     constexpr int CPR = D / 8;         // 16-byte chunks per row
-    constexpr int CH = BC * CPR / NT;  // chunks each thread stages per tensor per tile
-    static_assert(BC * CPR % NT == 0, "tile must split evenly over the threads");
-
-    __shared__ __attribute__((aligned(16))) uint16_t k_lds[BC * KSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t v_lds[BC * VSTR];
+    constexpr int RPI = 1024 / ROWB;   // rows written by one direct-to-LDS load instruction
+    constexpr int IPT = BC / RPI;      // such instructions per tile and tensor
+    constexpr int IPW = IPT / NW;      // ... per wavefront
+    static_assert(IPT % NW == 0, "tile loads must split evenly over the wavefronts");
+    // LDS: K buffer 0 | K buffer 1 | V buffer 0 | V buffer 1
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
@@ -113,6 +138,38 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
     const uint16_t* kh = k + head;
     const uint16_t* vh = v + head;
 
+    const int kv_end = CAUSAL ? (q0 + BR < S ? q0 + BR : S) : S;
+    const int ntiles = (kv_end + BC - 1) / BC;
+
+    // ---- direct-to-LDS tile loads ----
+    // instruction `inst` fills LDS bytes [inst*1024, +1024) of a tile buffer = rows inst*RPI.. ; lane
+    // writes chunk position lane%CPR of row lane/CPR and therefore fetches source chunk pos ^ swz(row)
+    uint32_t goff[IPW];
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+        const int r = (wave * IPW + i) * RPI + lane / CPR;
+        goff[i] = r * D + (((lane % CPR) ^ swz<D>(r)) << 3);
+    }
+    auto issue_loads = [&](int j0, int buf) {
+        const uint16_t* kt = kh + (size_t)j0 * D;
+        const uint16_t* vt = vh + (size_t)j0 * D;
+        const bool ragged = j0 + BC > S;
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+            const int inst = wave * IPW + i;
+            uint32_t off = goff[i];
+            if (ragged) {   // rows past the end are masked later; point them at the last valid row
+                const int over = j0 + inst * RPI + lane / CPR - (S - 1);
+                if (over > 0) off -= over * D;
+            }
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt + off),
+                                             (LDS_AS void*)(smem + buf * TILEB + inst * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vt + off),
+                                             (LDS_AS void*)(smem + (2 + buf) * TILEB + inst * 1024), 16, 0, 0);
+        }
+    };
+    issue_loads(0, 0);
+
     // Q^T operand, resident for the whole kernel: lane holds q[qrow][16 ks + 8 h .. +7]
     u32x4 qf[KSTEPS];
 #pragma unroll
@@ -120,31 +177,6 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
         qf[ks] = *(const u32x4*)(qh + (size_t)qrow_ld * D + 16 * ks + 8 * h);
         qf[ks] ^= qsign;   // a negative scale is folded into the sign of q (exact)
     }
-
-    const int kv_end = CAUSAL ? (q0 + BR < S ? q0 + BR : S) : S;
-    const int ntiles = (kv_end + BC - 1) / BC;
-
-    u32x4 kreg[CH], vreg[CH];
-    auto load_tile = [&](int j0) {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int idx = tid + i * NT;
-            const int row = idx / CPR, col = idx % CPR;
-            int grow = j0 + row;
-            grow = grow < S ? grow : S - 1;     // rows past the end are masked later; keep the address valid
-            kreg[i] = *(const u32x4*)(kh + (size_t)grow * D + col * 8);
-            vreg[i] = *(const u32x4*)(vh + (size_t)grow * D + col * 8);
-        }
-    };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int idx = tid + i * NT;
-            const int row = idx / CPR, col = idx % CPR;
-            *(u32x4*)(k_lds + row * KSTR + col * 8) = kreg[i];
-            *(u32x4*)(v_lds + row * VSTR + col * 8) = vreg[i];
-        }
-    };
 
     f32x16 acc_o[DB];
 #pragma unroll
@@ -154,20 +186,26 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
     float m_run = -INFINITY;   // running row maximum of the scaled logits, base-2 units
     float l_run = 0.f;         // this lane's share of the running row sum
 
-    // per-lane LDS offsets
-    const int k_off = l32 * KSTR + 8 * h;
-    const int v_off = (4 * h + ((lane & 15) >> 2)) * VSTR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    // ---- per-lane LDS byte offsets (loop invariant; tile/block parts are immediate offsets) ----
+    // K operand of (jb, ks): row 32 jb + l32, source chunk 2 ks + h
+    uint32_t kaddr[KSTEPS];
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) kaddr[ks] = l32 * ROWB + (((2 * ks + h) ^ swz<D>(l32)) << 4);
+    // V^T operand of (jb, t, half hi, block i): lane addresses 8 bytes of row 32 jb + 16 t + 8 hi + 4 h + x,
+    // elements 32 i + 16 g1 + 4 y .. +3, where x = (lane%16)/4, y = lane%4, g1 = (lane/16)%2
+    uint32_t vaddr[2][DB];
+    {
+        const int x = (lane & 15) >> 2, y = lane & 3, g1 = (lane >> 4) & 1;
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+            for (int i = 0; i < DB; ++i) {
+                const int chunk = 4 * i + 2 * g1 + (y >> 1);
+                vaddr[hi][i] = (4 * h + x) * ROWB + ((chunk ^ swz<D>(8 * hi + 4 * h + x)) << 4) + ((y & 1) << 3);
+            }
+    }
 
-    load_tile(0);
-    for (int t = 0; t < ntiles; ++t) {
-        const int j0 = t * BC;
-        __syncthreads();   // everyone is done reading the previous tile
-        store_tile();
-        __syncthreads();
-        if (t + 1 < ntiles) load_tile(j0 + BC);   // in flight while this tile is computed
-
-        if (CAUSAL && j0 > qw0 + 31) continue;    // every key of the tile is masked for this wavefront
-
+    auto compute_tile = [&](int j0, const uint8_t* kb, const uint8_t* vb) {
         // ---- S^T = K . Q^T ----
         f32x16 s[2];
 #pragma unroll
@@ -178,11 +216,11 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
         for (int ks = 0; ks < KSTEPS; ++ks)
 #pragma unroll
             for (int jb = 0; jb < 2; ++jb) {
-                u32x4 a = *(const u32x4*)(k_lds + k_off + 32 * jb * KSTR + 16 * ks);
+                u32x4 a = *(const u32x4*)(kb + kaddr[ks] + jb * 32 * ROWB);
                 s[jb] = E::mfma(a, qf[ks], s[jb]);
             }
 
-        // ---- mask, running maximum ----
+        // ---- mask, running maximum, exponentials ----
         const bool need_mask = (j0 + BC > S) || (CAUSAL && j0 + BC - 1 > qw0);
         float m_new;
         if (need_mask) {
@@ -219,19 +257,16 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
                 for (int r = 0; r < 16; ++r) s[jb][r] = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -m_new));
         }
 
-        // ---- running sum, rescale ----
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        // ---- running sum ----
+        // binary16 weights keep 11 bits, so the rounded weights can be summed two per dot instruction;
+        // bfloat16 keeps 8, which would cost the logsumexp its 1e-3 accuracy: sum those in fp32 first
         float psum = 0.f;
+        if (DT == 1) {
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+            for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) psum += s[jb][r];
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int i = 0; i < DB; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+                for (int r = 0; r < 16; ++r) psum += s[jb][r];
+        }
 
         // ---- P^T operands: registers 8t..8t+7 of block jb, rounded to the input type ----
         u32x4 pf[2][2];
@@ -241,6 +276,25 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
             for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) pf[jb][tt][e] = E::pack2(s[jb][8 * tt + 2 * e], s[jb][8 * tt + 2 * e + 1]);
+        if (DT == 0) {
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) psum = E::dot2_ones(pf[jb][tt][e], psum);
+        }
+
+        // ---- rescale only when some row of this wavefront got a new maximum ----
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run = l_run * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
+        }
+        m_run = m_new;
 
         // ---- O^T += V^T . P^T ----
 #pragma unroll
@@ -249,12 +303,25 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const uint16_t* __res
             for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int i = 0; i < DB; ++i) {
-                    const uint16_t* p = v_lds + v_off + (32 * jb + 16 * tt) * VSTR + 32 * i;
-                    u32x2 lo = lds_read_tr16(p);
-                    u32x2 hi = lds_read_tr16(p + 8 * VSTR);
+                    const uint8_t* p = vb + (32 * jb + 16 * tt) * ROWB;
+                    u32x2 lo = lds_read_tr16(p + vaddr[0][i]);
+                    u32x2 hi = lds_read_tr16(p + vaddr[1][i] + 8 * ROWB);
                     u32x4 a = {lo[0], lo[1], hi[0], hi[1]};
                     acc_o[i] = E::mfma(a, pf[jb][tt], acc_o[i]);
                 }
+    };
+
+    // one barrier per tile: after it, tile t has landed for everybody and nobody still reads the
+    // buffer that tile t+1 is about to overwrite
+    for (int t = 0; t < ntiles; t += 2) {
+        __syncthreads();
+        if (t + 1 < ntiles) issue_loads((t + 1) * BC, 1);
+        if (!(CAUSAL && t * BC > qw0 + 31)) compute_tile(t * BC, smem, smem + 2 * TILEB);
+        if (t + 1 < ntiles) {
+            __syncthreads();
+            if (t + 2 < ntiles) issue_loads((t + 2) * BC, 0);
+            if (!(CAUSAL && (t + 1) * BC > qw0 + 31)) compute_tile((t + 1) * BC, smem + TILEB, smem + 3 * TILEB);
+        }
     }
 
     // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
@@ -292,8 +359,9 @@ hipError_t launch(const AttnLaunch& a) {
     void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign};
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
-    return hipLaunchKernel(reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>), dim3((unsigned)blocks),
-                           dim3(NW * 64), args, 0, (hipStream_t)a.stream);
+    constexpr unsigned lds_bytes = 4u * ATTN_BC * 2u * D;   // two K and two V tile buffers
+    const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>);
+    return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(NW * 64), args, lds_bytes, (hipStream_t)a.stream);
 }
 
 }  // namespace

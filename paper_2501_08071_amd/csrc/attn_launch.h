@@ -7,6 +7,9 @@
 #define ATTN_NW 4   // wavefronts per workgroup; each owns 32 query rows
 #endif
 #define ATTN_BC 64  // keys per inner-loop tile
+#ifndef ATTN_WPE
+#define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
+#endif
 
 struct AttnLaunch {
     const void* q;
