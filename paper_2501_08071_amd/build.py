@@ -13,7 +13,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument"]
+         "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def build_lib(extra_flags=(), out: str = LIB, verbose: bool = False) -> str:

@@ -78,6 +78,16 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
     return __builtin_bit_cast(u32x2, t);
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l
+// (lds_base wave-uniform, a multiple of 16).  Written as asm so that the compiler's wait-count
+// insertion does not know about the transfer: it would otherwise wait for ALL outstanding tile
+// loads in front of LDS reads of the other buffer.  The wait is explicit, before the tile barrier.
+__device__ __forceinline__ void lds_dma16(uint32_t lds_base, const void* gbase, uint32_t byte_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(byte_off), "s"(gbase) : "memory", "m0");
+}
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // value held by the other half of the wavefront (lane l <-> lane l^32)
 __device__ __forceinline__ float other_half(float x) {
     uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -150,6 +160,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WP
         const int r = (wave * IPW + i) * RPI + lane / CPR;
         goff[i] = r * D + (((lane % CPR) ^ swz<D>(r)) << 3);
     }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)smem;
     auto issue_loads = [&](int j0, int buf) {
         const uint16_t* kt = kh + (size_t)j0 * D;
         const uint16_t* vt = vh + (size_t)j0 * D;
@@ -162,10 +173,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WP
                 const int over = j0 + inst * RPI + lane / CPR - (S - 1);
                 if (over > 0) off -= over * D;
             }
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kt + off),
-                                             (LDS_AS void*)(smem + buf * TILEB + inst * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vt + off),
-                                             (LDS_AS void*)(smem + (2 + buf) * TILEB + inst * 1024), 16, 0, 0);
+            lds_dma16(lds0 + buf * TILEB + inst * 1024, kt, off * 2);
+            lds_dma16(lds0 + (2 + buf) * TILEB + inst * 1024, vt, off * 2);
         }
     };
     issue_loads(0, 0);
@@ -314,10 +323,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WP
     // one barrier per tile: after it, tile t has landed for everybody and nobody still reads the
     // buffer that tile t+1 is about to overwrite
     for (int t = 0; t < ntiles; t += 2) {
+        wait_tile_loads();
         __syncthreads();
         if (t + 1 < ntiles) issue_loads((t + 1) * BC, 1);
         if (!(CAUSAL && t * BC > qw0 + 31)) compute_tile(t * BC, smem, smem + 2 * TILEB);
         if (t + 1 < ntiles) {
+            wait_tile_loads();
             __syncthreads();
             if (t + 2 < ntiles) issue_loads((t + 2) * BC, 0);
             if (!(CAUSAL && (t + 1) * BC > qw0 + 31)) compute_tile((t + 1) * BC, smem + TILEB, smem + 3 * TILEB);
