@@ -37,12 +37,12 @@ extern "C" const char* attn_kernel_name(int S, int D, int dtype, int causal) {
     static char names[2][2][2][64];
     char* n = names[dtype][D == 128][causal != 0];
     if (n[0] == 0)
-        std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d>", dtype, D, causal ? "true" : "false", ATTN_NW);
+        std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d, %d>", dtype, D, causal ? "true" : "false", ATTN_NW, ATTN_G);
     return n;
 }
 
 extern "C" int attn_tile_rows(int D, int dtype, int causal) {
-    return attn_supported(1, D, dtype, causal) ? ATTN_NW * 32 : 0;
+    return attn_supported(1, D, dtype, causal) ? ATTN_NW * 32 * ATTN_G : 0;
 }
 
 extern "C" int attn_tile_keys(int D, int dtype, int causal) {

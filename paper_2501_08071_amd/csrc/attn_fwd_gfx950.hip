@@ -7,13 +7,18 @@
 //
 // Work split
 //   workgroup = NW wavefronts, each owning 32 consecutive query rows of one (b,h);
-//   K/V stream through LDS in tiles of BC = 64 keys shared by the whole workgroup.
+//   K/V stream through LDS in blocks of BC = 32 keys shared by the whole workgroup.
 //
 // K/V movement
-//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), two buffers per tensor, the
-//   loads of tile t+1 issued right after the single barrier of tile t.  Such a load writes 1 KiB
+//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), four buffers per tensor,
+//   loads issued three blocks ahead of their use, one barrier per block.  Such a load writes 1 KiB
 //   of consecutive LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an
 //   XOR swizzle of the 16-byte chunk index within each row, applied on the global-address side.
+//
+// Software pipeline (per wavefront, one "slot" per key block k)
+//   matrix pipe:  S(k+1) = K(k+1).Q^T   and   O += V(k-1)^T.P(k-1)^T
+//   vector pipe:  P(k) = exp2(c S(k) - m)  (+ row sum, rounding to the input type)
+//   so neither product waits for the exponentials of its own block.
 //
 // Register layout (64-wide wavefront, lane l, half h = l/32, l32 = l%32)
 //   Everything is computed transposed so that one lane only ever holds values of ONE query row:
@@ -27,6 +32,7 @@
 //   Row maximum and row sum are an in-lane reduction plus one exchange between the halves.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "attn_launch.h"
 
@@ -73,8 +79,8 @@ template <> struct Elem<1> {  // bfloat16
 
 // 4 x 16-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
 // the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4 of its group.
-__device__ __forceinline__ u32x2 lds_read_tr16(const uint8_t* p) {
-    s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)p);
+__device__ __forceinline__ u32x2 lds_read_tr16(uint32_t addr) {
+    s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(uintptr_t)addr);
     return __builtin_bit_cast(u32x2, t);
 }
 
@@ -86,7 +92,10 @@ __device__ __forceinline__ void lds_dma16(uint32_t lds_base, const void* gbase, 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_base), "v"(byte_off), "s"(gbase) : "memory", "m0");
 }
-__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// wait until at most N of this wavefront's direct-to-LDS loads are still in flight (they land in order)
+template <int N>
+__device__ __forceinline__ void wait_block_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) { return *(const LDS_AS u32x4*)(uintptr_t)addr; }
 
 // value held by the other half of the wavefront (lane l <-> lane l^32)
 __device__ __forceinline__ float other_half(float x) {
@@ -110,25 +119,29 @@ __device__ __forceinline__ constexpr int swz(int row) {
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
-template <int DT, int D, bool CAUSAL, int NW>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WPE, ATTN_WPE))) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-                                                           const uint16_t* __restrict__ v, float* __restrict__ o,
-                                                           float* __restrict__ lse, int S, int BH, int nqt, float c,
-                                                           uint32_t qsign) {
+template <int DT, int D, bool CAUSAL, int NW, int G>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WPE, ATTN_WPE)))
+void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                     float* __restrict__ o, float* __restrict__ lse, int S, int BH, int nqt, float c_arg,
+                     uint32_t qsign) {
     using E = Elem<DT>;
-    constexpr int BR = NW * 32;        // query rows per workgroup
-    constexpr int BC = ATTN_BC;        // keys per tile
+    constexpr int WR = 32 * G;         // query rows per wavefront: G groups of 32
+    constexpr int BR = NW * WR;        // query rows per workgroup
+    constexpr int BC = ATTN_BC;        // keys per block
+    constexpr int NBUF = 4;            // LDS buffers per tensor; loads run NBUF-1 blocks ahead
     constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
     constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
     constexpr int ROWB = 2 * D;        // bytes per K/V row
-    constexpr int TILEB = BC * ROWB;   // bytes per tile
+    constexpr int BLKB = BC * ROWB;    // bytes per key block
     constexpr int CPR = D / 8;         // 16-byte chunks per row
     constexpr int RPI = 1024 / ROWB;   // rows written by one direct-to-LDS load instruction
-    constexpr int IPT = BC / RPI;      // such instructions per tile and tensor
-    constexpr int IPW = IPT / NW;      // ... per wavefront
-    static_assert(IPT % NW == 0, "tile loads must split evenly over the wavefronts");
-    // LDS: K buffer 0 | K buffer 1 | V buffer 0 | V buffer 1
+    constexpr int IPT = BC / RPI;      // such instructions per block and tensor
+    constexpr int IPW = IPT >= NW ? IPT / NW : 1;   // ... per loading wavefront
+    constexpr int LOADERS = IPT / IPW;              // wavefronts that issue loads
+    static_assert(BC == 32 && IPT % IPW == 0 && LOADERS <= NW, "load split");
+    // LDS: K buffers 0..3 | V buffers 0..3 ; block k lives in buffer k % 4
 
+    const float c = c_arg;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -139,9 +152,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WP
     const int bh = blockIdx.x % BH;
     const int qt = CAUSAL ? nqt - 1 - blockIdx.x / BH : blockIdx.x / BH;
     const int q0 = qt * BR;
-    const int qw0 = q0 + 32 * wave;          // first query row of this wavefront
-    const int qrow = qw0 + l32;              // this lane's query row (may lie beyond S on the last tile)
-    const int qrow_ld = qrow < S ? qrow : S - 1;
+    const int qw0 = q0 + WR * wave;          // first query row of this wavefront
 
     const size_t head = (size_t)bh * S * D;
     const uint16_t* qh = q + head;
@@ -149,58 +160,89 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WP
     const uint16_t* vh = v + head;
 
     const int kv_end = CAUSAL ? (q0 + BR < S ? q0 + BR : S) : S;
-    const int ntiles = (kv_end + BC - 1) / BC;
+    const int nblk = (kv_end + BC - 1) / BC;                      // key blocks the workgroup streams
+    // key blocks row group g of this wavefront computes on (later ones are fully masked for it)
+    auto group_blocks = [&](int g) {
+        if (!CAUSAL) return nblk;
+        const int mine = (qw0 + 32 * g) / BC + 1;
+        return mine < nblk ? mine : nblk;
+    };
 
-    // ---- direct-to-LDS tile loads ----
-    // instruction `inst` fills LDS bytes [inst*1024, +1024) of a tile buffer = rows inst*RPI.. ; lane
+    // ---- direct-to-LDS block loads ----
+    // instruction `inst` fills LDS bytes [inst*1024, +1024) of a block buffer = rows inst*RPI.. ; lane
     // writes chunk position lane%CPR of row lane/CPR and therefore fetches source chunk pos ^ swz(row)
-    uint32_t goff[IPW];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)smem;
+    uint32_t goff[IPW];   // byte offset of this lane's source chunk inside a block
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
         const int r = (wave * IPW + i) * RPI + lane / CPR;
-        goff[i] = r * D + (((lane % CPR) ^ swz<D>(r)) << 3);
+        goff[i] = (r * D + (((lane % CPR) ^ swz<D>(r)) << 3)) * 2;
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)smem;
-    auto issue_loads = [&](int j0, int buf) {
-        const uint16_t* kt = kh + (size_t)j0 * D;
-        const uint16_t* vt = vh + (size_t)j0 * D;
-        const bool ragged = j0 + BC > S;
+    // which = 0: K block -> K buffer blk % 4 ; which = 1: V block -> V buffer blk % 4
+    auto issue_load = [&](int which, int blk) {
+        if (LOADERS < NW && wave >= LOADERS) return;
+        const int j0 = blk * BC;
+        const uint16_t* src = (which ? vh : kh) + (size_t)j0 * D;
+        const uint32_t dst = lds0 + (NBUF * which + (blk & 3)) * BLKB + wave * IPW * 1024;
+        if (j0 + BC <= S) {
 #pragma unroll
-        for (int i = 0; i < IPW; ++i) {
-            const int inst = wave * IPW + i;
-            uint32_t off = goff[i];
-            if (ragged) {   // rows past the end are masked later; point them at the last valid row
-                const int over = j0 + inst * RPI + lane / CPR - (S - 1);
-                if (over > 0) off -= over * D;
+            for (int i = 0; i < IPW; ++i) lds_dma16(dst + i * 1024, src, goff[i]);
+        } else {   // rows past the end are masked later; point them at the last valid row
+#pragma unroll
+            for (int i = 0; i < IPW; ++i) {
+                const int over = j0 + (wave * IPW + i) * RPI + lane / CPR - (S - 1);
+                lds_dma16(dst + i * 1024, src, over > 0 ? goff[i] - over * ROWB : goff[i]);
             }
-            lds_dma16(lds0 + buf * TILEB + inst * 1024, kt, off * 2);
-            lds_dma16(lds0 + (2 + buf) * TILEB + inst * 1024, vt, off * 2);
         }
     };
-    issue_loads(0, 0);
+    // blocks K(0..3) and V(0..1) start the pipeline; slot k adds K(k+4) and V(k+2)
+    issue_load(0, 0);
+    if (1 < nblk) issue_load(0, 1);
+    issue_load(1, 0);
+    if (2 < nblk) issue_load(0, 2);
+    if (1 < nblk) issue_load(1, 1);
+    if (3 < nblk) issue_load(0, 3);
 
-    // Q^T operand, resident for the whole kernel: lane holds q[qrow][16 ks + 8 h .. +7]
-    u32x4 qf[KSTEPS];
+    // V buffer 3 is read by slot 0 (with all-zero weights) before anything was loaded into it:
+    // make its contents finite
+    {
+        constexpr int PER = BLKB / (NW * 64);
+        uint8_t* vb3 = smem + (2 * NBUF - 1) * BLKB + tid * PER;
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-        qf[ks] = *(const u32x4*)(qh + (size_t)qrow_ld * D + 16 * ks + 8 * h);
-        qf[ks] ^= qsign;   // a negative scale is folded into the sign of q (exact)
+        for (int i = 0; i < PER / 16; ++i) *(u32x4*)(vb3 + 16 * i) = u32x4{0u, 0u, 0u, 0u};
     }
 
-    f32x16 acc_o[DB];
+    // Q^T operands, resident for the whole kernel: lane holds q[row of group g][16 ks + 8 h .. +7]
+    u32x4 qf[G][KSTEPS];
 #pragma unroll
-    for (int i = 0; i < DB; ++i)
+    for (int g = 0; g < G; ++g) {
+        int row = qw0 + 32 * g + l32;
+        row = row < S ? row : S - 1;     // rows past the end: any valid row, never stored
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
-    float m_run = -INFINITY;   // running row maximum of the scaled logits, base-2 units
-    float l_run = 0.f;         // this lane's share of the running row sum
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            qf[g][ks] = *(const u32x4*)(qh + (size_t)row * D + 16 * ks + 8 * h);
+            qf[g][ks] ^= qsign;   // a negative scale is folded into the sign of q (exact)
+        }
+    }
 
-    // ---- per-lane LDS byte offsets (loop invariant; tile/block parts are immediate offsets) ----
-    // K operand of (jb, ks): row 32 jb + l32, source chunk 2 ks + h
+    f32x16 acc_o[G][DB];
+    float m_run[G], l_run[G];   // reference maximum (base-2 units) and this lane's share of the row sum
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m_run[g] = -INFINITY;
+        l_run[g] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[g][i][r] = 0.f;
+    }
+
+    // ---- per-lane LDS addresses (loop invariant; buffer parts become immediate offsets) ----
+    // K operand of step ks: row l32 of the block, source chunk 2 ks + h
     uint32_t kaddr[KSTEPS];
 #pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) kaddr[ks] = l32 * ROWB + (((2 * ks + h) ^ swz<D>(l32)) << 4);
-    // V^T operand of (jb, t, half hi, block i): lane addresses 8 bytes of row 32 jb + 16 t + 8 hi + 4 h + x,
+    for (int ks = 0; ks < KSTEPS; ++ks) kaddr[ks] = lds0 + l32 * ROWB + (((2 * ks + h) ^ swz<D>(l32)) << 4);
+    // V^T operand of (t, half hi, block i): lane addresses 8 bytes of row 16 t + 8 hi + 4 h + x,
     // elements 32 i + 16 g1 + 4 y .. +3, where x = (lane%16)/4, y = lane%4, g1 = (lane/16)%2
     uint32_t vaddr[2][DB];
     {
@@ -210,152 +252,268 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WP
 #pragma unroll
             for (int i = 0; i < DB; ++i) {
                 const int chunk = 4 * i + 2 * g1 + (y >> 1);
-                vaddr[hi][i] = (4 * h + x) * ROWB + ((chunk ^ swz<D>(8 * hi + 4 * h + x)) << 4) + ((y & 1) << 3);
+                vaddr[hi][i] = lds0 + NBUF * BLKB + (8 * hi + 4 * h + x) * ROWB +
+                               ((chunk ^ swz<D>(8 * hi + 4 * h + x)) << 4) + ((y & 1) << 3);
             }
     }
 
-    auto compute_tile = [&](int j0, const uint8_t* kb, const uint8_t* vb) {
-        // ---- S^T = K . Q^T ----
-        f32x16 s[2];
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[jb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks)
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb) {
-                u32x4 a = *(const u32x4*)(kb + kaddr[ks] + jb * 32 * ROWB);
-                s[jb] = E::mfma(a, qf[ks], s[jb]);
-            }
-
-        // ---- mask, running maximum, exponentials ----
-        const bool need_mask = (j0 + BC > S) || (CAUSAL && j0 + BC - 1 > qw0);
-        float m_new;
-        if (need_mask) {
-            // scale first, then mask, so that scale == 0 cannot meet an infinity
-            const int lim = (CAUSAL ? qrow_ld : S - 1) - j0 - 4 * h;
-            float mx = -INFINITY;
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int off = 32 * jb + 8 * (r / 4) + (r % 4);
-                    float x = s[jb][r] * c;
-                    x = off > lim ? -INFINITY : x;
-                    s[jb][r] = x;
-                    mx = fmaxf(mx, x);
-                }
-            mx = fmaxf(mx, other_half(mx));
-            m_new = fmaxf(m_run, mx);
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[jb][r] = __builtin_amdgcn_exp2f(s[jb][r] - m_new);
-        } else {
-            float mx = s[0][0];
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[jb][r]);
-            mx = fmaxf(mx, other_half(mx));
-            m_new = fmaxf(m_run, mx * c);    // c >= 0
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[jb][r] = __builtin_amdgcn_exp2f(fmaf(s[jb][r], c, -m_new));
-        }
-
-        // ---- running sum ----
-        // binary16 weights keep 11 bits, so the rounded weights can be summed two per dot instruction;
-        // bfloat16 keeps 8, which would cost the logsumexp its 1e-3 accuracy: sum those in fp32 first
-        float psum = 0.f;
-        if (DT == 1) {
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) psum += s[jb][r];
-        }
-
-        // ---- P^T operands: registers 8t..8t+7 of block jb, rounded to the input type ----
-        u32x4 pf[2][2];
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pf[jb][tt][e] = E::pack2(s[jb][8 * tt + 2 * e], s[jb][8 * tt + 2 * e + 1]);
-        if (DT == 0) {
-#pragma unroll
-            for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) psum = E::dot2_ones(pf[jb][tt][e], psum);
-        }
-
-        // ---- rescale only when some row of this wavefront got a new maximum ----
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        l_run = l_run * alpha + psum;
-        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
-#pragma unroll
-            for (int i = 0; i < DB; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
-        }
-        m_run = m_new;
-
-        // ---- O^T += V^T . P^T ----
-#pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int i = 0; i < DB; ++i) {
-                    const uint8_t* p = vb + (32 * jb + 16 * tt) * ROWB;
-                    u32x2 lo = lds_read_tr16(p + vaddr[0][i]);
-                    u32x2 hi = lds_read_tr16(p + vaddr[1][i] + 8 * ROWB);
-                    u32x4 a = {lo[0], lo[1], hi[0], hi[1]};
-                    acc_o[i] = E::mfma(a, pf[jb][tt], acc_o[i]);
-                }
+    // operand fetches: unit u < 2 DB is the V^T fragment (t = u / DB, i = u % DB) of V buffer VB,
+    // unit u >= 2 DB the K fragment of contraction step u - 2 DB of K buffer KB
+    constexpr int NU = 2 * DB + KSTEPS;
+    auto fetch_v = [&](int VB, int tt, int i) {
+        u32x2 lo = lds_read_tr16(vaddr[0][i] + VB * BLKB + 16 * tt * ROWB);
+        u32x2 hi = lds_read_tr16(vaddr[1][i] + VB * BLKB + 16 * tt * ROWB);
+        return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
 
-    // one barrier per tile: after it, tile t has landed for everybody and nobody still reads the
-    // buffer that tile t+1 is about to overwrite
-    for (int t = 0; t < ntiles; t += 2) {
-        wait_tile_loads();
-        __syncthreads();
-        if (t + 1 < ntiles) issue_loads((t + 1) * BC, 1);
-        if (!(CAUSAL && t * BC > qw0 + 31)) compute_tile(t * BC, smem, smem + 2 * TILEB);
-        if (t + 1 < ntiles) {
-            wait_tile_loads();
-            __syncthreads();
-            if (t + 2 < ntiles) issue_loads((t + 2) * BC, 0);
-            if (!(CAUSAL && (t + 1) * BC > qw0 + 31)) compute_tile((t + 1) * BC, smem + TILEB, smem + 3 * TILEB);
-        }
-    }
-
-    // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
-    const float l_tot = l_run + other_half(l_run);
-    const float inv = 1.0f / l_tot;
-    if (qrow < S) {
-        float* orow = o + head + (size_t)qrow * D;
+    // scale the accumulators of a row group whose reference maximum moved (rare after the first blocks)
+    auto rescale_o = [&](int g, float alpha) {
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 x = {acc_o[i][4 * g] * inv, acc_o[i][4 * g + 1] * inv, acc_o[i][4 * g + 2] * inv,
-                           acc_o[i][4 * g + 3] * inv};
-                *(f32x4*)(orow + 32 * i + 8 * g + 4 * h) = x;
+            for (int r = 0; r < 16; ++r) acc_o[g][i][r] *= alpha;
+    };
+
+    // O^T(g) += V(j)^T . P(j)^T, plain order
+    auto pv_plain = [&](int g, const u32x4 (&pf)[2], int VB) {
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int i = 0; i < DB; ++i) {
+                acc_o[g][i] = E::mfma(fetch_v(VB, tt, i), pf[tt], acc_o[g][i]);
+                __builtin_amdgcn_sched_barrier(0);   // no hoisting of all the reads: registers are scarce
             }
-        if (lse != nullptr && h == 0)
-            lse[(size_t)bh * S + qrow] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    };
+    // S^T(g) = K(j) . Q^T, plain order
+    auto qk_plain = [&](int g, f32x16& s, int KB) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            s = E::mfma(lds_read_b128(kaddr[ks] + KB * BLKB), qf[g][ks], s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // Softmax of a block that may be cut by the causal diagonal or by the end of the sequence:
+    // scale, mask, maximum, weights; plain order, nothing interleaved.
+    auto softmax_masked = [&](int g, const f32x16& s, u32x4 (&pf)[2], int j0) {
+        f32x16 p;
+        int qrow = qw0 + 32 * g + l32;
+        qrow = qrow < S ? qrow : S - 1;
+        // scale first, then mask, so that scale == 0 cannot meet an infinity
+        const int lim = (CAUSAL ? qrow : S - 1) - j0 - 4 * h;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int off = 8 * (r / 4) + (r % 4);
+            float x = s[r] * c;
+            x = off > lim ? -INFINITY : x;
+            p[r] = x;
+            mx = fmaxf(mx, x);
+        }
+        mx = fmaxf(mx, other_half(mx));
+        const float m_new = fmaxf(m_run[g], mx);
+        float psum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            p[r] = __builtin_amdgcn_exp2f(p[r] - m_new);
+            if (r % 2 == 1) {
+                const uint32_t w = E::pack2(p[r - 1], p[r]);
+                pf[r / 8][(r % 8) / 2] = w;
+                if (DT == 0) psum = E::dot2_ones(w, psum);
+            }
+            if (DT == 1) psum += p[r];
+        }
+        const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
+        l_run[g] = l_run[g] * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run[g]) != 0) rescale_o(g, alpha);
+        m_run[g] = m_new;
+    };
+
+    // start of slot k: wait for this wavefront's loads of K(k+1) and V(k-1) (issued three slots ago, so
+    // newer ones may stay in flight), barrier, then issue the loads of K(k+4) and V(k+2)
+    auto slot_sync = [&](int kb) {
+        if (kb + 3 < nblk && kb >= 2) wait_block_loads<4 * IPW>();
+        else if (kb + 3 < nblk && kb == 1) wait_block_loads<2 * IPW>();
+        else wait_block_loads<0>();
+        __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
+        if (kb + 4 < nblk) issue_load(0, kb + 4);
+        if (kb + 2 < nblk) issue_load(1, kb + 2);
+    };
+
+    // Slot k of the pipeline (PH = k % 4 fixes every LDS offset).  s_cur holds S(k) on entry, s_nxt
+    // receives S(k+1); pf_prv holds the weights of block k-1, pf_cur receives those of block k.
+    // Main-loop slots only: blocks that no wavefront of the workgroup needs a mask for, one straight line
+    // of hand-ordered code.
+    auto slot = [&](int kb, auto phase, f32x16 (&s_cur)[G], f32x16 (&s_nxt)[G], u32x4 (&pf_prv)[G][2],
+                    u32x4 (&pf_cur)[G][2]) {
+        constexpr int PH = decltype(phase)::value;
+        constexpr int KB = (PH + 1) & 3;   // buffer of K(k+1)
+        constexpr int VB = (PH + 3) & 3;   // buffer of V(k-1)
+        slot_sync(kb);
+        {
+            // Units 0 .. 2 DB - 1: O^T += V(k-1)^T.P(k-1)^T ; units 2 DB .. NU - 1: S(k+1) = K(k+1).Q^T (this
+            // order keeps the fewest registers alive: P(k-1) and S(k) die while S(k+1) and P(k) are born).
+            // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction per
+            // row group on the unit's operand, and a share of the vector work of block k -- unit 0 the
+            // row maxima, the others their part of the 16 G weights.  The order written here is the
+            // order issued: nothing moves across a unit.
+            f32x16 p[G];
+            float psum[G], m_new[G], neg_m[G];
+            u32x4 opnd[NU];
+            auto fetch = [&](auto unit) {
+                constexpr int U = decltype(unit)::value;
+                if constexpr (U >= 2 * DB) opnd[U] = lds_read_b128(kaddr[U - 2 * DB] + KB * BLKB);
+                else opnd[U] = fetch_v(VB, U / DB, U % DB);
+            };
+            auto weight = [&](int g, int r) {
+                p[g][r] = __builtin_amdgcn_exp2f(fmaf(s_cur[g][r], c, neg_m[g]));
+                if (r % 2 == 1) {
+                    uint32_t w = E::pack2(p[g][r - 1], p[g][r]);
+                    asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
+                    pf_cur[g][r / 8][(r % 8) / 2] = w;
+                    if (DT == 0) psum[g] = E::dot2_ones(w, psum[g]);
+                }
+                // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8
+                // bits, which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
+                if (DT == 1) psum[g] += p[g][r];
+            };
+            auto unit_step = [&](auto unit) {
+                constexpr int U = decltype(unit)::value;
+                if constexpr (U + ATTN_FETCH < NU) fetch(std::integral_constant<int, U + ATTN_FETCH>{});
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    if constexpr (U >= 2 * DB) {
+                        if constexpr (U == 2 * DB) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) s_nxt[g][r] = 0.f;
+                        }
+                        s_nxt[g] = E::mfma(opnd[U], qf[g][U - 2 * DB], s_nxt[g]);
+                    } else {
+                        acc_o[g][U % DB] = E::mfma(opnd[U], pf_prv[g][U / DB], acc_o[g][U % DB]);
+                    }
+                }
+                if constexpr (U == 0) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        float mx = s_cur[g][0];
+#pragma unroll
+                        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[g][r]);
+                        mx = fmaxf(mx, other_half(mx));
+                        m_new[g] = fmaxf(m_run[g], mx * c);    // c >= 0
+                        neg_m[g] = -m_new[g];
+                        psum[g] = 0.f;
+                    }
+                } else {
+                    // 16 weights per group over the remaining NU - 1 units, the later units taking the extra ones
+                    constexpr int lo = (16 * (U - 1)) / (NU - 1), hi = (16 * U) / (NU - 1);
+#pragma unroll
+                    for (int r = lo; r < hi; ++r)
+#pragma unroll
+                        for (int g = 0; g < G; ++g) weight(g, r);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            fetch(std::integral_constant<int, 0>{});
+            if constexpr (ATTN_FETCH > 1) fetch(std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            [&]<int... U>(std::integer_sequence<int, U...>) {
+                (unit_step(std::integral_constant<int, U>{}), ...);
+            }(std::make_integer_sequence<int, NU>{});
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new[g]);
+                l_run[g] = l_run[g] * alpha + psum[g];
+                if (__builtin_amdgcn_ballot_w64(m_new[g] != m_run[g]) != 0) rescale_o(g, alpha);
+                m_run[g] = m_new[g];
+            }
+        }
+    };
+
+    f32x16 s_a[G], s_b[G];
+    u32x4 pf_a[G][2], pf_b[G][2];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) pf_b[g][tt] = u32x4{0u, 0u, 0u, 0u};
+    // prologue: S(0)
+    wait_block_loads<0>();
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g) qk_plain(g, s_a[g], 0);
+
+    // main loop: blocks below the causal diagonal of the whole query tile / inside the sequence
+    int kfull = CAUSAL ? q0 / BC : S / BC;
+    kfull = kfull < nblk ? kfull : nblk;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
+    for (int k0 = 0; k0 < kfull; k0 += 4) {
+        slot(k0, P0{}, s_a, s_b, pf_b, pf_a);
+        if (k0 + 1 < kfull) slot(k0 + 1, P1{}, s_b, s_a, pf_a, pf_b);
+        if (k0 + 2 < kfull) slot(k0 + 2, P2{}, s_a, s_b, pf_b, pf_a);
+        if (k0 + 3 < kfull) slot(k0 + 3, P3{}, s_b, s_a, pf_a, pf_b);
+    }
+    // The remaining blocks (at most BR / 32 under the causal mask, at most one otherwise), in plain order
+    // and in place: S(k) lives in s_a, the weights awaiting their second product in pf_b.
+    if (kfull & 1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            s_a[g] = s_b[g];
+            pf_b[g][0] = pf_a[g][0];
+            pf_b[g][1] = pf_a[g][1];
+        }
+    }
+    for (int kb = kfull; kb < nblk; ++kb) {
+        slot_sync(kb);
+        const int KB = (kb + 1) & 3, VB = (kb + 3) & 3;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int nb_g = group_blocks(g);
+            if (kb < nb_g) {
+                pv_plain(g, pf_b[g], VB);                          // O += V(k-1)^T.P(k-1)^T, frees pf_b
+                softmax_masked(g, s_a[g], pf_b[g], kb * BC);       // P(k) from S(k), frees s_a
+                __builtin_amdgcn_sched_barrier(0);
+                qk_plain(g, s_a[g], KB);                           // S(k+1); unused past the group's last block
+            } else if (kb == nb_g) {
+                pv_plain(g, pf_b[g], VB);                          // the group's last block
+            }
+        }
+    }
+    // the second product of the very last block
+    wait_block_loads<0>();
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        if (group_blocks(g) == nblk) pv_plain(g, pf_b[g], (nblk - 1) & 3);
+
+    // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int qrow = qw0 + 32 * g + l32;
+        const float l_tot = l_run[g] + other_half(l_run[g]);
+        const float inv = 1.0f / l_tot;
+        if (qrow < S) {
+            float* orow = o + head + (size_t)qrow * D;
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    f32x4 x = {acc_o[g][i][4 * gg] * inv, acc_o[g][i][4 * gg + 1] * inv, acc_o[g][i][4 * gg + 2] * inv,
+                               acc_o[g][i][4 * gg + 3] * inv};
+                    *(f32x4*)(orow + 32 * i + 8 * gg + 4 * h) = x;
+                }
+            if (lse != nullptr && h == 0)
+                lse[(size_t)bh * S + qrow] = (m_run[g] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+        }
     }
 }
 
-template <int DT, int D, bool CAUSAL, int NW>
+template <int DT, int D, bool CAUSAL, int NW, int G>
 hipError_t launch(const AttnLaunch& a) {
-    constexpr int BR = NW * 32;
+    constexpr int BR = NW * 32 * G;
     const int nqt = (a.S + BR - 1) / BR;
     const long long blocks = (long long)nqt * a.BH;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
@@ -370,8 +528,8 @@ hipError_t launch(const AttnLaunch& a) {
     void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign};
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
-    constexpr unsigned lds_bytes = 4u * ATTN_BC * 2u * D;   // two K and two V tile buffers
-    const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>);
+    constexpr unsigned lds_bytes = 8u * ATTN_BC * 2u * D;   // four K and four V block buffers
+    const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW, G>);
     return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(NW * 64), args, lds_bytes, (hipStream_t)a.stream);
 }
 
@@ -380,7 +538,7 @@ hipError_t launch(const AttnLaunch& a) {
 // dispatch on (dtype, D, causal); arguments were validated by the caller
 hipError_t attn_launch(const AttnLaunch& a) {
 #define ATTN_CASE(DT, DD, CZ)                                       \
-    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW>(a);
+    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW, ATTN_G>(a);
     ATTN_CASE(0, 64, false)
     ATTN_CASE(0, 64, true)
     ATTN_CASE(0, 128, false)

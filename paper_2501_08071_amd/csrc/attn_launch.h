@@ -4,9 +4,15 @@
 #include <stdint.h>
 
 #ifndef ATTN_NW
-#define ATTN_NW 4   // wavefronts per workgroup; each owns 32 query rows
+#define ATTN_NW 4   // wavefronts per workgroup
 #endif
-#define ATTN_BC 64  // keys per inner-loop tile
+#ifndef ATTN_G
+#define ATTN_G 1    // groups of 32 query rows per wavefront
+#endif
+#define ATTN_BC 32  // keys per inner-loop block
+#ifndef ATTN_FETCH
+#define ATTN_FETCH 2  // matrix instructions between the LDS read of an operand and its use (1 or 2)
+#endif
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif
