@@ -178,22 +178,24 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         const int r = (wave * IPW + i) * RPI + lane / CPR;
         goff[i] = (r * D + (((lane % CPR) ^ swz<D>(r)) << 3)) * 2;
     }
-    // which = 0: K block -> K buffer blk % 4 ; which = 1: V block -> V buffer blk % 4
-    auto issue_load = [&](int which, int blk) {
+    // One load instruction: piece i (0..IPW-1) of K block `blk` (which = 0) or V block `blk` (which = 1)
+    // into buffer blk % 4 of that tensor.  Issuing such an instruction holds the wavefront until the
+    // memory pipeline accepts it, so the main loop spreads the pieces between its matrix instructions.
+    auto issue_piece = [&](int which, int blk, int i) {
         if (LOADERS < NW && wave >= LOADERS) return;
         const int j0 = blk * BC;
         const uint16_t* src = (which ? vh : kh) + (size_t)j0 * D;
-        const uint32_t dst = lds0 + (NBUF * which + (blk & 3)) * BLKB + wave * IPW * 1024;
-        if (j0 + BC <= S) {
-#pragma unroll
-            for (int i = 0; i < IPW; ++i) lds_dma16(dst + i * 1024, src, goff[i]);
-        } else {   // rows past the end are masked later; point them at the last valid row
-#pragma unroll
-            for (int i = 0; i < IPW; ++i) {
-                const int over = j0 + (wave * IPW + i) * RPI + lane / CPR - (S - 1);
-                lds_dma16(dst + i * 1024, src, over > 0 ? goff[i] - over * ROWB : goff[i]);
-            }
+        const uint32_t dst = lds0 + (NBUF * which + (blk & 3)) * BLKB + (wave * IPW + i) * 1024;
+        uint32_t off = goff[i];
+        if (j0 + BC > S) {   // rows past the end are masked later; point them at the last valid row
+            const int over = j0 + (wave * IPW + i) * RPI + lane / CPR - (S - 1);
+            if (over > 0) off -= over * ROWB;
         }
+        lds_dma16(dst, src, off);
+    };
+    auto issue_load = [&](int which, int blk) {
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) issue_piece(which, blk, i);
     };
     // blocks K(0..3) and V(0..1) start the pipeline; slot k adds K(k+4) and V(k+2)
     issue_load(0, 0);
@@ -333,13 +335,15 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 
     // start of slot k: wait for this wavefront's loads of K(k+1) and V(k-1) (issued three slots ago, so
     // newer ones may stay in flight), barrier, then issue the loads of K(k+4) and V(k+2)
-    auto slot_sync = [&](int kb) {
+    auto slot_sync = [&](int kb, bool issue) {
         if (kb + 3 < nblk && kb >= 2) wait_block_loads<4 * IPW>();
         else if (kb + 3 < nblk && kb == 1) wait_block_loads<2 * IPW>();
         else wait_block_loads<0>();
         __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
-        if (kb + 4 < nblk) issue_load(0, kb + 4);
-        if (kb + 2 < nblk) issue_load(1, kb + 2);
+        if (issue) {
+            if (kb + 4 < nblk) issue_load(0, kb + 4);
+            if (kb + 2 < nblk) issue_load(1, kb + 2);
+        }
     };
 
     // Slot k of the pipeline (PH = k % 4 fixes every LDS offset).  s_cur holds S(k) on entry, s_nxt
@@ -351,7 +355,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         constexpr int PH = decltype(phase)::value;
         constexpr int KB = (PH + 1) & 3;   // buffer of K(k+1)
         constexpr int VB = (PH + 3) & 3;   // buffer of V(k-1)
-        slot_sync(kb);
+        slot_sync(kb, false);
         {
             // Units 0 .. 2 DB - 1: O^T += V(k-1)^T.P(k-1)^T ; units 2 DB .. NU - 1: S(k+1) = K(k+1).Q^T (this
             // order keeps the fewest registers alive: P(k-1) and S(k) die while S(k+1) and P(k) are born).
@@ -400,8 +404,12 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                         float mx = s_cur[g][0];
 #pragma unroll
                         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[g][r]);
-                        mx = fmaxf(mx, other_half(mx));
-                        m_new[g] = fmaxf(m_run[g], mx * c);    // c >= 0
+                        mx = fmaxf(mx, other_half(mx)) * c;    // c >= 0
+                        // The reference maximum only moves when the true one has outgrown it by more than
+                        // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32
+                        // rows per group SOME row sets a new maximum in most blocks, and following every
+                        // one would rescale all accumulators nearly every block.
+                        m_new[g] = mx > m_run[g] + ATTN_MAX_SLACK ? mx : m_run[g];
                         neg_m[g] = -m_new[g];
                         psum[g] = 0.f;
                     }
@@ -413,10 +421,17 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #pragma unroll
                         for (int g = 0; g < G; ++g) weight(g, r);
                 }
+                // the 2 IPW load instructions of this slot (K(k+4), V(k+2)), one per unit, evenly spread
+                constexpr int NP = 2 * IPW, GAP = NU / NP;
+                if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
+                    constexpr int P = U / GAP;
+                    if (P < IPW ? kb + 4 < nblk : kb + 2 < nblk) issue_piece(P / IPW, P < IPW ? kb + 4 : kb + 2, P % IPW);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             };
-            fetch(std::integral_constant<int, 0>{});
-            if constexpr (ATTN_FETCH > 1) fetch(std::integral_constant<int, 1>{});
+            [&]<int... U>(std::integer_sequence<int, U...>) {
+                (fetch(std::integral_constant<int, U>{}), ...);
+            }(std::make_integer_sequence<int, ATTN_FETCH>{});
             __builtin_amdgcn_sched_barrier(0);
             [&]<int... U>(std::integer_sequence<int, U...>) {
                 (unit_step(std::integral_constant<int, U>{}), ...);
@@ -467,7 +482,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         }
     }
     for (int kb = kfull; kb < nblk; ++kb) {
-        slot_sync(kb);
+        slot_sync(kb, true);
         const int KB = (kb + 1) & 3, VB = (kb + 3) & 3;
 #pragma unroll
         for (int g = 0; g < G; ++g) {

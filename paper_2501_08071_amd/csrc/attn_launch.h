@@ -10,6 +10,9 @@
 #define ATTN_G 1    // groups of 32 query rows per wavefront
 #endif
 #define ATTN_BC 32  // keys per inner-loop block
+#ifndef ATTN_MAX_SLACK
+#define ATTN_MAX_SLACK 8.0f  // log2 of the largest softmax weight tolerated before the reference maximum is moved
+#endif
 #ifndef ATTN_FETCH
 #define ATTN_FETCH 2  // matrix instructions between the LDS read of an operand and its use (1 or 2)
 #endif
