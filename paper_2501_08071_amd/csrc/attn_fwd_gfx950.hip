@@ -128,7 +128,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int WR = 32 * G;         // query rows per wavefront: G groups of 32
     constexpr int BR = NW * WR;        // query rows per workgroup
     constexpr int BC = ATTN_BC;        // keys per block
-    constexpr int NBUF = 4;            // LDS buffers per tensor; loads run NBUF-1 blocks ahead
+    constexpr int NBUF = ATTN_NBUF;    // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
+    constexpr int KAHEAD = NBUF;       // slot k issues the load of K(k + KAHEAD) ...
+    constexpr int VAHEAD = NBUF - 2;   // ... and of V(k + VAHEAD); both land NBUF - 1 slots before their use
     constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
     constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
     constexpr int ROWB = 2 * D;        // bytes per K/V row
@@ -139,7 +141,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int IPW = IPT >= NW ? IPT / NW : 1;   // ... per loading wavefront
     constexpr int LOADERS = IPT / IPW;              // wavefronts that issue loads
     static_assert(BC == 32 && IPT % IPW == 0 && LOADERS <= NW, "load split");
-    // LDS: K buffers 0..3 | V buffers 0..3 ; block k lives in buffer k % 4
+    // LDS: K buffers 0..NBUF-1 | V buffers 0..NBUF-1
 
     const float c = c_arg;
     const int tid = threadIdx.x;
@@ -185,7 +187,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         if (LOADERS < NW && wave >= LOADERS) return;
         const int j0 = blk * BC;
         const uint16_t* src = (which ? vh : kh) + (size_t)j0 * D;
-        const uint32_t dst = lds0 + (NBUF * which + (blk & 3)) * BLKB + (wave * IPW + i) * 1024;
+        const uint32_t dst = lds0 + (NBUF * which + (blk & (NBUF - 1))) * BLKB + (wave * IPW + i) * 1024;
         uint32_t off = goff[i];
         if (j0 + BC > S) {   // rows past the end are masked later; point them at the last valid row
             const int over = j0 + (wave * IPW + i) * RPI + lane / CPR - (S - 1);
@@ -197,15 +199,15 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #pragma unroll
         for (int i = 0; i < IPW; ++i) issue_piece(which, blk, i);
     };
-    // blocks K(0..3) and V(0..1) start the pipeline; slot k adds K(k+4) and V(k+2)
+    // blocks K(0 .. KAHEAD-1) and V(0 .. VAHEAD-1) start the pipeline, in the order of their use;
+    // slot k adds K(k + KAHEAD) and V(k + VAHEAD)
     issue_load(0, 0);
-    if (1 < nblk) issue_load(0, 1);
-    issue_load(1, 0);
-    if (2 < nblk) issue_load(0, 2);
-    if (1 < nblk) issue_load(1, 1);
-    if (3 < nblk) issue_load(0, 3);
-
-    // V buffer 3 is read by slot 0 (with all-zero weights) before anything was loaded into it:
+#pragma unroll
+    for (int j = 1; j < KAHEAD; ++j) {
+        if (j < nblk) issue_load(0, j);
+        if (j - 1 < VAHEAD && j - 1 < nblk) issue_load(1, j - 1);
+    }
+    // the last V buffer is read by slot 0 (with all-zero weights) before anything was loaded into it:
     // make its contents finite
     {
         constexpr int PER = BLKB / (NW * 64);
@@ -229,6 +231,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 
     f32x16 acc_o[G][DB];
     float m_run[G], l_run[G];   // reference maximum (base-2 units) and this lane's share of the row sum
+    float m_ref[G], m_nxt[G];   // main loop: reference maximum of the block in hand / of the next one
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         m_run[g] = -INFINITY;
@@ -336,13 +339,12 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // start of slot k: wait for this wavefront's loads of K(k+1) and V(k-1) (issued three slots ago, so
     // newer ones may stay in flight), barrier, then issue the loads of K(k+4) and V(k+2)
     auto slot_sync = [&](int kb, bool issue) {
-        if (kb + 3 < nblk && kb >= 2) wait_block_loads<4 * IPW>();
-        else if (kb + 3 < nblk && kb == 1) wait_block_loads<2 * IPW>();
+        if (kb + KAHEAD < nblk) wait_block_loads<(NBUF - 2) * 2 * IPW>();
         else wait_block_loads<0>();
         __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
         if (issue) {
-            if (kb + 4 < nblk) issue_load(0, kb + 4);
-            if (kb + 2 < nblk) issue_load(1, kb + 2);
+            if (kb + KAHEAD < nblk) issue_load(0, kb + KAHEAD);
+            if (kb + VAHEAD < nblk) issue_load(1, kb + VAHEAD);
         }
     };
 
@@ -353,23 +355,29 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     auto slot = [&](int kb, auto phase, f32x16 (&s_cur)[G], f32x16 (&s_nxt)[G], u32x4 (&pf_prv)[G][2],
                     u32x4 (&pf_cur)[G][2]) {
         constexpr int PH = decltype(phase)::value;
-        constexpr int KB = (PH + 1) & 3;   // buffer of K(k+1)
-        constexpr int VB = (PH + 3) & 3;   // buffer of V(k-1)
+        constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
+        constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
         slot_sync(kb, false);
         {
-            // Units 0 .. 2 DB - 1: O^T += V(k-1)^T.P(k-1)^T ; units 2 DB .. NU - 1: S(k+1) = K(k+1).Q^T (this
-            // order keeps the fewest registers alive: P(k-1) and S(k) die while S(k+1) and P(k) are born).
+            // Units 0 .. KSTEPS - 1: S(k+1) = K(k+1).Q^T ; units KSTEPS .. NU - 1: O^T += V(k-1)^T.P(k-1)^T.
             // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction per
-            // row group on the unit's operand, and a share of the vector work of block k -- unit 0 the
-            // row maxima, the others their part of the 16 G weights.  The order written here is the
-            // order issued: nothing moves across a unit.
+            // row group on the unit's operand, and a share of the vector work: every unit its part of the
+            // 16 G weights of block k (their reference maximum m_ref was fixed during the previous slot,
+            // so the exponentials start at once), and, once S(k+1) is complete, the row maxima of block
+            // k+1 for the next slot.  The order written here is the order issued: nothing moves across a
+            // unit.
             f32x16 p[G];
-            float psum[G], m_new[G], neg_m[G];
+            float psum[G], neg_m[G], mx[G];
             u32x4 opnd[NU];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                neg_m[g] = -m_ref[g];
+                psum[g] = 0.f;
+            }
             auto fetch = [&](auto unit) {
                 constexpr int U = decltype(unit)::value;
-                if constexpr (U >= 2 * DB) opnd[U] = lds_read_b128(kaddr[U - 2 * DB] + KB * BLKB);
-                else opnd[U] = fetch_v(VB, U / DB, U % DB);
+                if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
+                else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
             };
             auto weight = [&](int g, int r) {
                 p[g][r] = __builtin_amdgcn_exp2f(fmaf(s_cur[g][r], c, neg_m[g]));
@@ -383,49 +391,60 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                 // bits, which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
                 if (DT == 1) psum[g] += p[g][r];
             };
+            // row maximum of S(k+1): 8 three-input maxima, spread over the units after its last matrix
+            // instruction (CH0 leaves that instruction time to retire), finished one unit later
+            constexpr int CH0 = KSTEPS + 1, NCH = DB == 4 ? 4 : 2, OPS = 8 / NCH;
+            auto max_op = [&](int g, int j) {
+                if (j == 0) mx[g] = fmaxf(fmaxf(s_nxt[g][0], s_nxt[g][1]), s_nxt[g][2]);
+                else if (j < 7) mx[g] = fmaxf(fmaxf(mx[g], s_nxt[g][2 * j + 1]), s_nxt[g][2 * j + 2]);
+                else mx[g] = fmaxf(mx[g], s_nxt[g][15]);
+            };
             auto unit_step = [&](auto unit) {
                 constexpr int U = decltype(unit)::value;
                 if constexpr (U + ATTN_FETCH < NU) fetch(std::integral_constant<int, U + ATTN_FETCH>{});
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    if constexpr (U >= 2 * DB) {
-                        if constexpr (U == 2 * DB) {
+                    if constexpr (U < KSTEPS) {
+                        if constexpr (U == 0) {
 #pragma unroll
                             for (int r = 0; r < 16; ++r) s_nxt[g][r] = 0.f;
                         }
-                        s_nxt[g] = E::mfma(opnd[U], qf[g][U - 2 * DB], s_nxt[g]);
+                        s_nxt[g] = E::mfma(opnd[U], qf[g][U], s_nxt[g]);
                     } else {
-                        acc_o[g][U % DB] = E::mfma(opnd[U], pf_prv[g][U / DB], acc_o[g][U % DB]);
+                        constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
+                        acc_o[g][i] = E::mfma(opnd[U], pf_prv[g][tt], acc_o[g][i]);
                     }
                 }
-                if constexpr (U == 0) {
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        float mx = s_cur[g][0];
-#pragma unroll
-                        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[g][r]);
-                        mx = fmaxf(mx, other_half(mx)) * c;    // c >= 0
-                        // The reference maximum only moves when the true one has outgrown it by more than
-                        // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32
-                        // rows per group SOME row sets a new maximum in most blocks, and following every
-                        // one would rescale all accumulators nearly every block.
-                        m_new[g] = mx > m_run[g] + ATTN_MAX_SLACK ? mx : m_run[g];
-                        neg_m[g] = -m_new[g];
-                        psum[g] = 0.f;
-                    }
-                } else {
-                    // 16 weights per group over the remaining NU - 1 units, the later units taking the extra ones
-                    constexpr int lo = (16 * (U - 1)) / (NU - 1), hi = (16 * U) / (NU - 1);
+                {
+                    constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
 #pragma unroll
                     for (int r = lo; r < hi; ++r)
 #pragma unroll
                         for (int g = 0; g < G; ++g) weight(g, r);
                 }
-                // the 2 IPW load instructions of this slot (K(k+4), V(k+2)), one per unit, evenly spread
+                if constexpr (U >= CH0 && U < CH0 + NCH) {
+#pragma unroll
+                    for (int j = (U - CH0) * OPS; j < (U - CH0 + 1) * OPS; ++j)
+#pragma unroll
+                        for (int g = 0; g < G; ++g) max_op(g, j);
+                }
+                if constexpr (U == CH0 + NCH) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float m = fmaxf(mx[g], other_half(mx[g])) * c;    // c >= 0
+                        // The reference maximum only moves when the true one has outgrown it by more than
+                        // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32
+                        // rows per group SOME row sets a new maximum in most blocks, and following every
+                        // one would rescale all accumulators nearly every block.
+                        m_nxt[g] = m > m_ref[g] + ATTN_MAX_SLACK ? m : m_ref[g];
+                    }
+                }
+                // the 2 IPW load instructions of this slot, one per unit, evenly spread
                 constexpr int NP = 2 * IPW, GAP = NU / NP;
                 if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
                     constexpr int P = U / GAP;
-                    if (P < IPW ? kb + 4 < nblk : kb + 2 < nblk) issue_piece(P / IPW, P < IPW ? kb + 4 : kb + 2, P % IPW);
+                    if (P < IPW ? kb + KAHEAD < nblk : kb + VAHEAD < nblk)
+                        issue_piece(P / IPW, P < IPW ? kb + KAHEAD : kb + VAHEAD, P % IPW);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             };
@@ -436,12 +455,14 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             [&]<int... U>(std::integer_sequence<int, U...>) {
                 (unit_step(std::integral_constant<int, U>{}), ...);
             }(std::make_integer_sequence<int, NU>{});
+            // block k is done: its weights were taken against m_ref; everything older against m_run
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new[g]);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_ref[g]);
                 l_run[g] = l_run[g] * alpha + psum[g];
-                if (__builtin_amdgcn_ballot_w64(m_new[g] != m_run[g]) != 0) rescale_o(g, alpha);
-                m_run[g] = m_new[g];
+                if (__builtin_amdgcn_ballot_w64(m_ref[g] != m_run[g]) != 0) rescale_o(g, alpha);
+                m_run[g] = m_ref[g];
+                m_ref[g] = m_nxt[g];
             }
         }
     };
@@ -456,20 +477,26 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     wait_block_loads<0>();
     __syncthreads();
 #pragma unroll
-    for (int g = 0; g < G; ++g) qk_plain(g, s_a[g], 0);
+    for (int g = 0; g < G; ++g) {
+        qk_plain(g, s_a[g], 0);
+        float mx = s_a[g][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[g][r]);
+        m_ref[g] = fmaxf(mx, other_half(mx)) * c;   // only used if block 0 goes through the main loop
+        m_nxt[g] = m_ref[g];
+    }
 
     // main loop: blocks below the causal diagonal of the whole query tile / inside the sequence
     int kfull = CAUSAL ? q0 / BC : S / BC;
     kfull = kfull < nblk ? kfull : nblk;
-    using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
-    using P2 = std::integral_constant<int, 2>;
-    using P3 = std::integral_constant<int, 3>;
-    for (int k0 = 0; k0 < kfull; k0 += 4) {
-        slot(k0, P0{}, s_a, s_b, pf_b, pf_a);
-        if (k0 + 1 < kfull) slot(k0 + 1, P1{}, s_b, s_a, pf_a, pf_b);
-        if (k0 + 2 < kfull) slot(k0 + 2, P2{}, s_a, s_b, pf_b, pf_a);
-        if (k0 + 3 < kfull) slot(k0 + 3, P3{}, s_b, s_a, pf_a, pf_b);
+    for (int k0 = 0; k0 < kfull; k0 += NBUF) {
+        [&]<int... PH>(std::integer_sequence<int, PH...>) {
+            ((k0 + PH < kfull
+                  ? (PH % 2 == 0 ? slot(k0 + PH, std::integral_constant<int, PH>{}, s_a, s_b, pf_b, pf_a)
+                                 : slot(k0 + PH, std::integral_constant<int, PH>{}, s_b, s_a, pf_a, pf_b))
+                  : (void)0),
+             ...);
+        }(std::make_integer_sequence<int, NBUF>{});
     }
     // The remaining blocks (at most BR / 32 under the causal mask, at most one otherwise), in plain order
     // and in place: S(k) lives in s_a, the weights awaiting their second product in pf_b.
@@ -483,7 +510,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     }
     for (int kb = kfull; kb < nblk; ++kb) {
         slot_sync(kb, true);
-        const int KB = (kb + 1) & 3, VB = (kb + 3) & 3;
+        const int KB = (kb + 1) & (NBUF - 1), VB = (kb + NBUF - 1) & (NBUF - 1);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int nb_g = group_blocks(g);
@@ -502,7 +529,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     __syncthreads();
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        if (group_blocks(g) == nblk) pv_plain(g, pf_b[g], (nblk - 1) & 3);
+        if (group_blocks(g) == nblk) pv_plain(g, pf_b[g], (nblk - 1) & (NBUF - 1));
 
     // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
 #pragma unroll
@@ -543,8 +570,16 @@ hipError_t launch(const AttnLaunch& a) {
     void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign};
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
-    constexpr unsigned lds_bytes = 8u * ATTN_BC * 2u * D;   // four K and four V block buffers
+    constexpr unsigned lds_bytes = 2u * ATTN_NBUF * ATTN_BC * 2u * D;   // NBUF K and NBUF V block buffers
     const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW, G>);
+    if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
     return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(NW * 64), args, lds_bytes, (hipStream_t)a.stream);
 }
 

@@ -13,8 +13,11 @@
 #ifndef ATTN_MAX_SLACK
 #define ATTN_MAX_SLACK 8.0f  // log2 of the largest softmax weight tolerated before the reference maximum is moved
 #endif
+#ifndef ATTN_NBUF
+#define ATTN_NBUF 4   // LDS buffers per tensor: 4 (two workgroups per CU at D = 128) or 8
+#endif
 #ifndef ATTN_FETCH
-#define ATTN_FETCH 2  // matrix instructions between the LDS read of an operand and its use (1 or 2)
+#define ATTN_FETCH 4  // units between the LDS read of an operand and the matrix instruction that uses it
 #endif
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
