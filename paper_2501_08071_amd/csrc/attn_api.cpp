@@ -37,12 +37,12 @@ extern "C" const char* attn_kernel_name(int S, int D, int dtype, int causal) {
     static char names[2][2][2][64];
     char* n = names[dtype][D == 128][causal != 0];
     if (n[0] == 0)
-        std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d, %d>", dtype, D, causal ? "true" : "false", ATTN_NW, ATTN_G);
+        std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d>", dtype, D, causal ? "true" : "false", ATTN_NW);
     return n;
 }
 
 extern "C" int attn_tile_rows(int D, int dtype, int causal) {
-    return attn_supported(1, D, dtype, causal) ? ATTN_NW * 32 * ATTN_G : 0;
+    return attn_supported(1, D, dtype, causal) ? ATTN_NW * 32 : 0;
 }
 
 extern "C" int attn_tile_keys(int D, int dtype, int causal) {
@@ -65,7 +65,10 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, f
     a.BH = (int)bh; a.S = S; a.D = D;
     a.causal = causal != 0;
     a.dtype = dtype;
-    a.c = std::fabs(scale) * 1.4426950408889634f;
+    // |scale| * log2(e), kept off zero: the kernel masks logits with a huge finite number, which has
+    // to stay far below the real ones after the multiplication (at 1e-30 every real logit is still 0
+    // to fp32, so scale == 0 keeps its meaning)
+    a.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     a.qsign = std::signbit(scale) && scale != 0.f ? 0x80008000u : 0u;
     a.stream = stream;
     const hipError_t err = attn_launch(a);

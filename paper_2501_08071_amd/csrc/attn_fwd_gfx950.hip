@@ -119,14 +119,13 @@ __device__ __forceinline__ constexpr int swz(int row) {
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
-template <int DT, int D, bool CAUSAL, int NW, int G>
+template <int DT, int D, bool CAUSAL, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WPE, ATTN_WPE)))
 void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                      float* __restrict__ o, float* __restrict__ lse, int S, int BH, int nqt, float c_arg,
                      uint32_t qsign) {
     using E = Elem<DT>;
-    constexpr int WR = 32 * G;         // query rows per wavefront: G groups of 32
-    constexpr int BR = NW * WR;        // query rows per workgroup
+    constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
     constexpr int BC = ATTN_BC;        // keys per block
     constexpr int NBUF = ATTN_NBUF;    // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
     constexpr int KAHEAD = NBUF;       // slot k issues the load of K(k + KAHEAD) ...
@@ -154,7 +153,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const int bh = blockIdx.x % BH;
     const int qt = CAUSAL ? nqt - 1 - blockIdx.x / BH : blockIdx.x / BH;
     const int q0 = qt * BR;
-    const int qw0 = q0 + WR * wave;          // first query row of this wavefront
+    const int qw0 = q0 + 32 * wave;          // first query row of this wavefront
+    const int qrow = qw0 + l32;              // this lane's query row (may lie beyond S on the last tile)
+    const int qrow_ld = qrow < S ? qrow : S - 1;
 
     const size_t head = (size_t)bh * S * D;
     const uint16_t* qh = q + head;
@@ -162,13 +163,17 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const uint16_t* vh = v + head;
 
     const int kv_end = CAUSAL ? (q0 + BR < S ? q0 + BR : S) : S;
-    const int nblk = (kv_end + BC - 1) / BC;                      // key blocks the workgroup streams
-    // key blocks row group g of this wavefront computes on (later ones are fully masked for it)
-    auto group_blocks = [&](int g) {
-        if (!CAUSAL) return nblk;
-        const int mine = (qw0 + 32 * g) / BC + 1;
-        return mine < nblk ? mine : nblk;
+    const int nblk = (kv_end + BC - 1) / BC;       // key blocks the workgroup streams
+    // kd: the first block this wavefront needs a mask for -- the one on its causal diagonal, or the
+    // ragged last block of the sequence (which may not exist: then kd == nblk).  Later blocks of the
+    // workgroup are masked entirely for it.
+    const int nfull = S / BC;
+    auto first_masked = [&](int w) {
+        const int d = CAUSAL ? q0 / BC + w : nfull;
+        return d < nfull ? d : nfull;
     };
+    const int kd = first_masked(wave);
+    const int last_max = nblk - 1;   // the last block any wavefront of the workgroup works on
 
     // ---- direct-to-LDS block loads ----
     // instruction `inst` fills LDS bytes [inst*1024, +1024) of a block buffer = rows inst*RPI.. ; lane
@@ -181,7 +186,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         goff[i] = (r * D + (((lane % CPR) ^ swz<D>(r)) << 3)) * 2;
     }
     // One load instruction: piece i (0..IPW-1) of K block `blk` (which = 0) or V block `blk` (which = 1)
-    // into buffer blk % 4 of that tensor.  Issuing such an instruction holds the wavefront until the
+    // into buffer blk % NBUF of that tensor.  Issuing such an instruction holds the wavefront until the
     // memory pipeline accepts it, so the main loop spreads the pieces between its matrix instructions.
     auto issue_piece = [&](int which, int blk, int i) {
         if (LOADERS < NW && wave >= LOADERS) return;
@@ -207,6 +212,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         if (j < nblk) issue_load(0, j);
         if (j - 1 < VAHEAD && j - 1 < nblk) issue_load(1, j - 1);
     }
+
     // the last V buffer is read by slot 0 (with all-zero weights) before anything was loaded into it:
     // make its contents finite
     {
@@ -216,31 +222,22 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         for (int i = 0; i < PER / 16; ++i) *(u32x4*)(vb3 + 16 * i) = u32x4{0u, 0u, 0u, 0u};
     }
 
-    // Q^T operands, resident for the whole kernel: lane holds q[row of group g][16 ks + 8 h .. +7]
-    u32x4 qf[G][KSTEPS];
+    // Q^T operand, resident for the whole kernel: lane holds q[qrow][16 ks + 8 h .. +7]
+    u32x4 qf[KSTEPS];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        int row = qw0 + 32 * g + l32;
-        row = row < S ? row : S - 1;     // rows past the end: any valid row, never stored
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            qf[g][ks] = *(const u32x4*)(qh + (size_t)row * D + 16 * ks + 8 * h);
-            qf[g][ks] ^= qsign;   // a negative scale is folded into the sign of q (exact)
-        }
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+        qf[ks] = *(const u32x4*)(qh + (size_t)qrow_ld * D + 16 * ks + 8 * h);
+        qf[ks] ^= qsign;   // a negative scale is folded into the sign of q (exact)
     }
 
-    f32x16 acc_o[G][DB];
-    float m_run[G], l_run[G];   // reference maximum (base-2 units) and this lane's share of the row sum
-    float m_ref[G], m_nxt[G];   // main loop: reference maximum of the block in hand / of the next one
+    f32x16 acc_o[DB];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        m_run[g] = -INFINITY;
-        l_run[g] = 0.f;
+    for (int i = 0; i < DB; ++i)
 #pragma unroll
-        for (int i = 0; i < DB; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[g][i][r] = 0.f;
-    }
+        for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
+    float m_run = -INFINITY;   // reference maximum (base-2 units) everything accumulated so far was taken against
+    float l_run = 0.f;         // this lane's share of the running row sum
+    float m_ref, m_nxt;        // main loop: reference maximum of the block in hand / of the next one
 
     // ---- per-lane LDS addresses (loop invariant; buffer parts become immediate offsets) ----
     // K operand of step ks: row l32 of the block, source chunk 2 ks + h
@@ -262,300 +259,210 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
     }
 
-    // operand fetches: unit u < 2 DB is the V^T fragment (t = u / DB, i = u % DB) of V buffer VB,
-    // unit u >= 2 DB the K fragment of contraction step u - 2 DB of K buffer KB
-    constexpr int NU = 2 * DB + KSTEPS;
+    constexpr int NU = KSTEPS + 2 * DB;   // units (operand fetches) per slot
     auto fetch_v = [&](int VB, int tt, int i) {
         u32x2 lo = lds_read_tr16(vaddr[0][i] + VB * BLKB + 16 * tt * ROWB);
         u32x2 hi = lds_read_tr16(vaddr[1][i] + VB * BLKB + 16 * tt * ROWB);
         return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
 
-    // scale the accumulators of a row group whose reference maximum moved (rare after the first blocks)
-    auto rescale_o = [&](int g, float alpha) {
+    // scale the accumulators when the reference maximum of some row moved (rare after the first blocks)
+    auto rescale_o = [&](float alpha) {
 #pragma unroll
         for (int i = 0; i < DB; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[g][i][r] *= alpha;
+            for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
     };
 
-    // O^T(g) += V(j)^T . P(j)^T, plain order
-    auto pv_plain = [&](int g, const u32x4 (&pf)[2], int VB) {
+    // O^T += V(j)^T . P(j)^T, plain order (used once or twice per wavefront)
+    auto pv_plain = [&](const u32x4 (&pf)[2], int VB) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int i = 0; i < DB; ++i) {
-                acc_o[g][i] = E::mfma(fetch_v(VB, tt, i), pf[tt], acc_o[g][i]);
+                acc_o[i] = E::mfma(fetch_v(VB, tt, i), pf[tt], acc_o[i]);
                 __builtin_amdgcn_sched_barrier(0);   // no hoisting of all the reads: registers are scarce
             }
     };
-    // S^T(g) = K(j) . Q^T, plain order
-    auto qk_plain = [&](int g, f32x16& s, int KB) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            s = E::mfma(lds_read_b128(kaddr[ks] + KB * BLKB), qf[g][ks], s);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
 
-    // Softmax of a block that may be cut by the causal diagonal or by the end of the sequence:
-    // scale, mask, maximum, weights; plain order, nothing interleaved.
-    auto softmax_masked = [&](int g, const f32x16& s, u32x4 (&pf)[2], int j0) {
-        f32x16 p;
-        int qrow = qw0 + 32 * g + l32;
-        qrow = qrow < S ? qrow : S - 1;
-        // scale first, then mask, so that scale == 0 cannot meet an infinity
-        const int lim = (CAUSAL ? qrow : S - 1) - j0 - 4 * h;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int off = 8 * (r / 4) + (r % 4);
-            float x = s[r] * c;
-            x = off > lim ? -INFINITY : x;
-            p[r] = x;
-            mx = fmaxf(mx, x);
-        }
-        mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m_run[g], mx);
-        float psum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            p[r] = __builtin_amdgcn_exp2f(p[r] - m_new);
-            if (r % 2 == 1) {
-                const uint32_t w = E::pack2(p[r - 1], p[r]);
-                pf[r / 8][(r % 8) / 2] = w;
-                if (DT == 0) psum = E::dot2_ones(w, psum);
-            }
-            if (DT == 1) psum += p[r];
-        }
-        const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_new);
-        l_run[g] = l_run[g] * alpha + psum;
-        if (__builtin_amdgcn_ballot_w64(m_new != m_run[g]) != 0) rescale_o(g, alpha);
-        m_run[g] = m_new;
-    };
-
-    // start of slot k: wait for this wavefront's loads of K(k+1) and V(k-1) (issued three slots ago, so
-    // newer ones may stay in flight), barrier, then issue the loads of K(k+4) and V(k+2)
-    auto slot_sync = [&](int kb, bool issue) {
-        if (kb + KAHEAD < nblk) wait_block_loads<(NBUF - 2) * 2 * IPW>();
-        else wait_block_loads<0>();
-        __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
-        if (issue) {
-            if (kb + KAHEAD < nblk) issue_load(0, kb + KAHEAD);
-            if (kb + VAHEAD < nblk) issue_load(1, kb + VAHEAD);
-        }
-    };
-
-    // Slot k of the pipeline (PH = k % 4 fixes every LDS offset).  s_cur holds S(k) on entry, s_nxt
-    // receives S(k+1); pf_prv holds the weights of block k-1, pf_cur receives those of block k.
-    // Main-loop slots only: blocks that no wavefront of the workgroup needs a mask for, one straight line
-    // of hand-ordered code.
-    auto slot = [&](int kb, auto phase, f32x16 (&s_cur)[G], f32x16 (&s_nxt)[G], u32x4 (&pf_prv)[G][2],
-                    u32x4 (&pf_cur)[G][2]) {
+    // Slot k of the pipeline (PH = k % NBUF fixes every LDS offset).  Every wavefront: wait for its own
+    // loads of K(k+1) and V(k-1) (issued NBUF-1 slots ago, so newer ones may stay in flight), barrier.
+    // Then one straight line for every wavefront and every block: s_cur holds S(k) on entry, s_nxt
+    // receives S(k+1); pf_prv holds the weights of block k-1, pf_cur receives those of block k.  From
+    // block kd on the masked logits are first replaced by a huge negative number; past the causal
+    // diagonal that is all of them, the weights come out as zeros and the slot changes nothing (the
+    // wavefront would otherwise only wait for the others at the next barrier).
+    auto slot = [&](int kb, auto phase, f32x16& s_cur, f32x16& s_nxt, u32x4 (&pf_prv)[2], u32x4 (&pf_cur)[2]) {
         constexpr int PH = decltype(phase)::value;
         constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
         constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
-        slot_sync(kb, false);
-        {
-            // Units 0 .. KSTEPS - 1: S(k+1) = K(k+1).Q^T ; units KSTEPS .. NU - 1: O^T += V(k-1)^T.P(k-1)^T.
-            // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction per
-            // row group on the unit's operand, and a share of the vector work: every unit its part of the
-            // 16 G weights of block k (their reference maximum m_ref was fixed during the previous slot,
-            // so the exponentials start at once), and, once S(k+1) is complete, the row maxima of block
-            // k+1 for the next slot.  The order written here is the order issued: nothing moves across a
-            // unit.
-            f32x16 p[G];
-            float psum[G], neg_m[G], mx[G];
-            u32x4 opnd[NU];
+        if (kb + KAHEAD < nblk) wait_block_loads<(NBUF - 2) * 2 * IPW>();
+        else wait_block_loads<0>();
+        __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
+
+        if (kb >= kd) {
+            // A block cut by the causal diagonal or by the end of the sequence: masked logits become
+            // -3e38 (times c >= 1e-30 that is far below any real logit and the weight comes out as an
+            // exact 0), and the reference maximum is taken again, over what is left.
+            const int lim = (CAUSAL ? qrow_ld : S - 1) - kb * BC - 4 * h;
+            float m = -3.0e38f;
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                neg_m[g] = -m_ref[g];
-                psum[g] = 0.f;
+            for (int r = 0; r < 16; ++r) {
+                const int off = 8 * (r / 4) + (r % 4);
+                s_cur[r] = off > lim ? -3.0e38f : s_cur[r];
+                m = fmaxf(m, s_cur[r]);
             }
-            auto fetch = [&](auto unit) {
-                constexpr int U = decltype(unit)::value;
-                if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
-                else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
-            };
-            auto weight = [&](int g, int r) {
-                p[g][r] = __builtin_amdgcn_exp2f(fmaf(s_cur[g][r], c, neg_m[g]));
-                if (r % 2 == 1) {
-                    uint32_t w = E::pack2(p[g][r - 1], p[g][r]);
-                    asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
-                    pf_cur[g][r / 8][(r % 8) / 2] = w;
-                    if (DT == 0) psum[g] = E::dot2_ones(w, psum[g]);
-                }
-                // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8
-                // bits, which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
-                if (DT == 1) psum[g] += p[g][r];
-            };
-            // row maximum of S(k+1): 8 three-input maxima, spread over the units after its last matrix
-            // instruction (CH0 leaves that instruction time to retire), finished one unit later
-            constexpr int CH0 = KSTEPS + 1, NCH = DB == 4 ? 4 : 2, OPS = 8 / NCH;
-            auto max_op = [&](int g, int j) {
-                if (j == 0) mx[g] = fmaxf(fmaxf(s_nxt[g][0], s_nxt[g][1]), s_nxt[g][2]);
-                else if (j < 7) mx[g] = fmaxf(fmaxf(mx[g], s_nxt[g][2 * j + 1]), s_nxt[g][2 * j + 2]);
-                else mx[g] = fmaxf(mx[g], s_nxt[g][15]);
-            };
-            auto unit_step = [&](auto unit) {
-                constexpr int U = decltype(unit)::value;
-                if constexpr (U + ATTN_FETCH < NU) fetch(std::integral_constant<int, U + ATTN_FETCH>{});
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    if constexpr (U < KSTEPS) {
-                        if constexpr (U == 0) {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) s_nxt[g][r] = 0.f;
-                        }
-                        s_nxt[g] = E::mfma(opnd[U], qf[g][U], s_nxt[g]);
-                    } else {
-                        constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
-                        acc_o[g][i] = E::mfma(opnd[U], pf_prv[g][tt], acc_o[g][i]);
-                    }
-                }
-                {
-                    constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
-#pragma unroll
-                    for (int r = lo; r < hi; ++r)
-#pragma unroll
-                        for (int g = 0; g < G; ++g) weight(g, r);
-                }
-                if constexpr (U >= CH0 && U < CH0 + NCH) {
-#pragma unroll
-                    for (int j = (U - CH0) * OPS; j < (U - CH0 + 1) * OPS; ++j)
-#pragma unroll
-                        for (int g = 0; g < G; ++g) max_op(g, j);
-                }
-                if constexpr (U == CH0 + NCH) {
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const float m = fmaxf(mx[g], other_half(mx[g])) * c;    // c >= 0
-                        // The reference maximum only moves when the true one has outgrown it by more than
-                        // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32
-                        // rows per group SOME row sets a new maximum in most blocks, and following every
-                        // one would rescale all accumulators nearly every block.
-                        m_nxt[g] = m > m_ref[g] + ATTN_MAX_SLACK ? m : m_ref[g];
-                    }
-                }
-                // the 2 IPW load instructions of this slot, one per unit, evenly spread
-                constexpr int NP = 2 * IPW, GAP = NU / NP;
-                if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
-                    constexpr int P = U / GAP;
-                    if (P < IPW ? kb + KAHEAD < nblk : kb + VAHEAD < nblk)
-                        issue_piece(P / IPW, P < IPW ? kb + KAHEAD : kb + VAHEAD, P % IPW);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            };
-            [&]<int... U>(std::integer_sequence<int, U...>) {
-                (fetch(std::integral_constant<int, U>{}), ...);
-            }(std::make_integer_sequence<int, ATTN_FETCH>{});
-            __builtin_amdgcn_sched_barrier(0);
-            [&]<int... U>(std::integer_sequence<int, U...>) {
-                (unit_step(std::integral_constant<int, U>{}), ...);
-            }(std::make_integer_sequence<int, NU>{});
-            // block k is done: its weights were taken against m_ref; everything older against m_run
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float alpha = __builtin_amdgcn_exp2f(m_run[g] - m_ref[g]);
-                l_run[g] = l_run[g] * alpha + psum[g];
-                if (__builtin_amdgcn_ballot_w64(m_ref[g] != m_run[g]) != 0) rescale_o(g, alpha);
-                m_run[g] = m_ref[g];
-                m_ref[g] = m_nxt[g];
-            }
+            m = fmaxf(m, other_half(m)) * c;
+            m_ref = m > m_run + ATTN_MAX_SLACK ? m : m_run;
         }
+        // Units 0 .. KSTEPS - 1: S(k+1) = K(k+1).Q^T ; units KSTEPS .. NU - 1: O^T += V(k-1)^T.P(k-1)^T.
+        // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction on the
+        // unit's operand, and a share of the vector work: every unit its part of the 16 weights of block
+        // k (their reference maximum m_ref was fixed during the previous slot, so the exponentials start
+        // at once), and, once S(k+1) is complete, the row maximum of block k+1 for the next slot.  The
+        // order written here is the order issued: nothing moves across a unit.
+        f32x16 p;
+        float psum = 0.f, mx = 0.f;
+        const float neg_m = -m_ref;
+        u32x4 opnd[NU];
+        auto fetch = [&](auto unit) {
+            constexpr int U = decltype(unit)::value;
+            if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
+            else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
+        };
+        auto weight = [&](int r) {
+            p[r] = __builtin_amdgcn_exp2f(fmaf(s_cur[r], c, neg_m));
+            if (r % 2 == 1) {
+                uint32_t w = E::pack2(p[r - 1], p[r]);
+                asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
+                pf_cur[r / 8][(r % 8) / 2] = w;
+                if (DT == 0) psum = E::dot2_ones(w, psum);
+            }
+            // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
+            // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
+            if (DT == 1) psum += p[r];
+        };
+        // row maximum of S(k+1): 8 three-input maxima, spread over the units after its last matrix
+        // instruction (CH0 leaves that instruction time to retire), finished one unit later
+        constexpr int CH0 = KSTEPS + 1, NCH = DB == 4 ? 4 : 2, OPS = 8 / NCH;
+        auto max_op = [&](int j) {
+            if (j == 0) mx = fmaxf(fmaxf(s_nxt[0], s_nxt[1]), s_nxt[2]);
+            else if (j < 7) mx = fmaxf(fmaxf(mx, s_nxt[2 * j + 1]), s_nxt[2 * j + 2]);
+            else mx = fmaxf(mx, s_nxt[15]);
+        };
+        auto unit_step = [&](auto unit) {
+            constexpr int U = decltype(unit)::value;
+            if constexpr (U + ATTN_FETCH < NU) fetch(std::integral_constant<int, U + ATTN_FETCH>{});
+            if constexpr (U < KSTEPS) {
+                if constexpr (U == 0) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+                }
+                s_nxt = E::mfma(opnd[U], qf[U], s_nxt);
+            } else {
+                constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
+                acc_o[i] = E::mfma(opnd[U], pf_prv[tt], acc_o[i]);
+            }
+            {
+                constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
+#pragma unroll
+                for (int r = lo; r < hi; ++r) weight(r);
+            }
+            if constexpr (U >= CH0 && U < CH0 + NCH) {
+#pragma unroll
+                for (int j = (U - CH0) * OPS; j < (U - CH0 + 1) * OPS; ++j) max_op(j);
+            }
+            if constexpr (U == CH0 + NCH) {
+                const float m = fmaxf(mx, other_half(mx)) * c;    // c >= 0
+                // The reference maximum only moves when the true one has outgrown it by more than
+                // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32 rows per
+                // wavefront SOME row sets a new maximum in most blocks, and following every one would
+                // rescale all accumulators nearly every block.
+                m_nxt = m > m_ref + ATTN_MAX_SLACK ? m : m_ref;
+            }
+            // the 2 IPW load instructions of this slot, one per unit, evenly spread
+            constexpr int NP = 2 * IPW, GAP = NU / NP;
+            if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
+                constexpr int P = U / GAP;
+                if (P < IPW ? kb + KAHEAD < nblk : kb + VAHEAD < nblk)
+                    issue_piece(P / IPW, P < IPW ? kb + KAHEAD : kb + VAHEAD, P % IPW);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        [&]<int... U>(std::integer_sequence<int, U...>) {
+            (fetch(std::integral_constant<int, U>{}), ...);
+        }(std::make_integer_sequence<int, ATTN_FETCH>{});
+        __builtin_amdgcn_sched_barrier(0);
+        [&]<int... U>(std::integer_sequence<int, U...>) {
+            (unit_step(std::integral_constant<int, U>{}), ...);
+        }(std::make_integer_sequence<int, NU>{});
+        // block k is done: its weights were taken against m_ref; everything older against m_run
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
+        l_run = l_run * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(m_ref != m_run) != 0) rescale_o(alpha);
+        m_run = m_ref;
+        m_ref = m_nxt;
     };
 
-    f32x16 s_a[G], s_b[G];
-    u32x4 pf_a[G][2], pf_b[G][2];
+    f32x16 s_a, s_b;
+    u32x4 pf_a[2], pf_b[2];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) pf_b[g][tt] = u32x4{0u, 0u, 0u, 0u};
-    // prologue: S(0)
+    for (int tt = 0; tt < 2; ++tt) pf_b[tt] = u32x4{0u, 0u, 0u, 0u};
+    // prologue: S(0) and its row maximum
     wait_block_loads<0>();
     __syncthreads();
+    {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        qk_plain(g, s_a[g], 0);
-        float mx = s_a[g][0];
+        for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[g][r]);
-        m_ref[g] = fmaxf(mx, other_half(mx)) * c;   // only used if block 0 goes through the main loop
-        m_nxt[g] = m_ref[g];
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            s_a = E::mfma(lds_read_b128(kaddr[ks]), qf[ks], s_a);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        float mx = s_a[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[r]);
+        m_ref = fmaxf(mx, other_half(mx)) * c;   // only used if block 0 goes through the main loop
+        m_nxt = m_ref;
     }
 
-    // main loop: blocks below the causal diagonal of the whole query tile / inside the sequence
-    int kfull = CAUSAL ? q0 / BC : S / BC;
-    kfull = kfull < nblk ? kfull : nblk;
-    for (int k0 = 0; k0 < kfull; k0 += NBUF) {
+    // main loop: one slot per block, up to the last block of the workgroup's last wavefront
+    for (int k0 = 0; k0 <= last_max; k0 += NBUF) {
         [&]<int... PH>(std::integer_sequence<int, PH...>) {
-            ((k0 + PH < kfull
+            ((k0 + PH <= last_max
                   ? (PH % 2 == 0 ? slot(k0 + PH, std::integral_constant<int, PH>{}, s_a, s_b, pf_b, pf_a)
                                  : slot(k0 + PH, std::integral_constant<int, PH>{}, s_b, s_a, pf_a, pf_b))
                   : (void)0),
              ...);
         }(std::make_integer_sequence<int, NBUF>{});
     }
-    // The remaining blocks (at most BR / 32 under the causal mask, at most one otherwise), in plain order
-    // and in place: S(k) lives in s_a, the weights awaiting their second product in pf_b.
-    if (kfull & 1) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            s_a[g] = s_b[g];
-            pf_b[g][0] = pf_a[g][0];
-            pf_b[g][1] = pf_a[g][1];
-        }
-    }
-    for (int kb = kfull; kb < nblk; ++kb) {
-        slot_sync(kb, true);
-        const int KB = (kb + 1) & (NBUF - 1), VB = (kb + NBUF - 1) & (NBUF - 1);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const int nb_g = group_blocks(g);
-            if (kb < nb_g) {
-                pv_plain(g, pf_b[g], VB);                          // O += V(k-1)^T.P(k-1)^T, frees pf_b
-                softmax_masked(g, s_a[g], pf_b[g], kb * BC);       // P(k) from S(k), frees s_a
-                __builtin_amdgcn_sched_barrier(0);
-                qk_plain(g, s_a[g], KB);                           // S(k+1); unused past the group's last block
-            } else if (kb == nb_g) {
-                pv_plain(g, pf_b[g], VB);                          // the group's last block
-            }
-        }
-    }
-    // the second product of the very last block
+    // The second product of the last block is still open; its weights sit in pf_a / pf_b by parity.
     wait_block_loads<0>();
     __syncthreads();
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-        if (group_blocks(g) == nblk) pv_plain(g, pf_b[g], (nblk - 1) & (NBUF - 1));
+    if (last_max & 1) pv_plain(pf_b, last_max & (NBUF - 1));
+    else pv_plain(pf_a, last_max & (NBUF - 1));
 
     // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
+    const float l_tot = l_run + other_half(l_run);
+    const float inv = 1.0f / l_tot;
+    if (qrow < S) {
+        float* orow = o + head + (size_t)qrow * D;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const int qrow = qw0 + 32 * g + l32;
-        const float l_tot = l_run[g] + other_half(l_run[g]);
-        const float inv = 1.0f / l_tot;
-        if (qrow < S) {
-            float* orow = o + head + (size_t)qrow * D;
+        for (int i = 0; i < DB; ++i)
 #pragma unroll
-            for (int i = 0; i < DB; ++i)
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    f32x4 x = {acc_o[g][i][4 * gg] * inv, acc_o[g][i][4 * gg + 1] * inv, acc_o[g][i][4 * gg + 2] * inv,
-                               acc_o[g][i][4 * gg + 3] * inv};
-                    *(f32x4*)(orow + 32 * i + 8 * gg + 4 * h) = x;
-                }
-            if (lse != nullptr && h == 0)
-                lse[(size_t)bh * S + qrow] = (m_run[g] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
-        }
+            for (int gg = 0; gg < 4; ++gg) {
+                f32x4 x = {acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv, acc_o[i][4 * gg + 2] * inv,
+                           acc_o[i][4 * gg + 3] * inv};
+                *(f32x4*)(orow + 32 * i + 8 * gg + 4 * h) = x;
+            }
+        if (lse != nullptr && h == 0)
+            lse[(size_t)bh * S + qrow] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     }
 }
 
-template <int DT, int D, bool CAUSAL, int NW, int G>
+template <int DT, int D, bool CAUSAL, int NW>
 hipError_t launch(const AttnLaunch& a) {
-    constexpr int BR = NW * 32 * G;
+    constexpr int BR = NW * 32;
     const int nqt = (a.S + BR - 1) / BR;
     const long long blocks = (long long)nqt * a.BH;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
@@ -571,7 +478,7 @@ hipError_t launch(const AttnLaunch& a) {
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
     constexpr unsigned lds_bytes = 2u * ATTN_NBUF * ATTN_BC * 2u * D;   // NBUF K and NBUF V block buffers
-    const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW, G>);
+    const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>);
     if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
         static bool raised = false;
         if (!raised) {
@@ -588,7 +495,7 @@ hipError_t launch(const AttnLaunch& a) {
 // dispatch on (dtype, D, causal); arguments were validated by the caller
 hipError_t attn_launch(const AttnLaunch& a) {
 #define ATTN_CASE(DT, DD, CZ)                                       \
-    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW, ATTN_G>(a);
+    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW>(a);
     ATTN_CASE(0, 64, false)
     ATTN_CASE(0, 64, true)
     ATTN_CASE(0, 128, false)

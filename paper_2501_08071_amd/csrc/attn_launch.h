@@ -4,10 +4,7 @@
 #include <stdint.h>
 
 #ifndef ATTN_NW
-#define ATTN_NW 4   // wavefronts per workgroup
-#endif
-#ifndef ATTN_G
-#define ATTN_G 1    // groups of 32 query rows per wavefront
+#define ATTN_NW 4   // wavefronts per workgroup, each owning 32 query rows
 #endif
 #define ATTN_BC 32  // keys per inner-loop block
 #ifndef ATTN_MAX_SLACK
