@@ -97,6 +97,18 @@ template <int N>
 __device__ __forceinline__ void wait_block_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) { return *(const LDS_AS u32x4*)(uintptr_t)addr; }
 
+// plain maxima, without the quiet-NaN canonicalisation the C library semantics would add
+__device__ __forceinline__ float vmax(float a, float b) {
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 // value held by the other half of the wavefront (lane l <-> lane l^32)
 __device__ __forceinline__ float other_half(float x) {
     uint32_t u = __builtin_bit_cast(uint32_t, x);
@@ -185,32 +197,36 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         const int r = (wave * IPW + i) * RPI + lane / CPR;
         goff[i] = (r * D + (((lane % CPR) ^ swz<D>(r)) << 3)) * 2;
     }
+    // the same for the ragged last block of the sequence: rows past the end (masked later) point at the
+    // last valid row
+    uint32_t goff_r[IPW];
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+        const int over = nfull * BC + (wave * IPW + i) * RPI + lane / CPR - (S - 1);
+        goff_r[i] = over > 0 ? goff[i] - over * ROWB : goff[i];
+    }
+    const uint32_t lds_wave = lds0 + wave * IPW * 1024;
     // One load instruction: piece i (0..IPW-1) of K block `blk` (which = 0) or V block `blk` (which = 1)
-    // into buffer blk % NBUF of that tensor.  Issuing such an instruction holds the wavefront until the
-    // memory pipeline accepts it, so the main loop spreads the pieces between its matrix instructions.
-    auto issue_piece = [&](int which, int blk, int i) {
+    // into LDS at lds_wave + dst.  A block index past the end of the stream is replaced by the last
+    // block (a copy nobody reads, into a buffer nobody needs any more), so that every slot issues the
+    // same number of loads and the code has no branch; the address arithmetic is scalar.
+    auto issue_piece = [&](int which, int blk, int i, uint32_t dst) {
         if (LOADERS < NW && wave >= LOADERS) return;
-        const int j0 = blk * BC;
-        const uint16_t* src = (which ? vh : kh) + (size_t)j0 * D;
-        const uint32_t dst = lds0 + (NBUF * which + (blk & (NBUF - 1))) * BLKB + (wave * IPW + i) * 1024;
-        uint32_t off = goff[i];
-        if (j0 + BC > S) {   // rows past the end are masked later; point them at the last valid row
-            const int over = j0 + (wave * IPW + i) * RPI + lane / CPR - (S - 1);
-            if (over > 0) off -= over * ROWB;
-        }
-        lds_dma16(dst, src, off);
+        const int b = blk < nblk - 1 ? blk : nblk - 1;
+        const uint16_t* src = (which ? vh : kh) + (size_t)b * (BC * D);
+        lds_dma16(lds_wave + dst, src, b >= nfull ? goff_r[i] : goff[i]);
     };
     auto issue_load = [&](int which, int blk) {
 #pragma unroll
-        for (int i = 0; i < IPW; ++i) issue_piece(which, blk, i);
+        for (int i = 0; i < IPW; ++i) issue_piece(which, blk, i, (NBUF * which + (blk & (NBUF - 1))) * BLKB + i * 1024);
     };
     // blocks K(0 .. KAHEAD-1) and V(0 .. VAHEAD-1) start the pipeline, in the order of their use;
     // slot k adds K(k + KAHEAD) and V(k + VAHEAD)
     issue_load(0, 0);
 #pragma unroll
     for (int j = 1; j < KAHEAD; ++j) {
-        if (j < nblk) issue_load(0, j);
-        if (j - 1 < VAHEAD && j - 1 < nblk) issue_load(1, j - 1);
+        issue_load(0, j);
+        if (j - 1 < VAHEAD) issue_load(1, j - 1);
     }
 
     // the last V buffer is read by slot 0 (with all-zero weights) before anything was loaded into it:
@@ -296,8 +312,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         constexpr int PH = decltype(phase)::value;
         constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
         constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
-        if (kb + KAHEAD < nblk) wait_block_loads<(NBUF - 2) * 2 * IPW>();
-        else wait_block_loads<0>();
+        wait_block_loads<(NBUF - 2) * 2 * IPW>();
         __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
 
         if (kb >= kd) {
@@ -340,15 +355,18 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
             // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
             // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
-            if (DT == 1) psum += p[r];
+            if (DT == 1) {
+                psum += p[r];
+                asm volatile("" : "+v"(psum));   // add here, under the matrix instruction, not later
+            }
         };
         // row maximum of S(k+1): 8 three-input maxima, spread over the units after its last matrix
         // instruction (CH0 leaves that instruction time to retire), finished one unit later
         constexpr int CH0 = KSTEPS + 1, NCH = DB == 4 ? 4 : 2, OPS = 8 / NCH;
         auto max_op = [&](int j) {
-            if (j == 0) mx = fmaxf(fmaxf(s_nxt[0], s_nxt[1]), s_nxt[2]);
-            else if (j < 7) mx = fmaxf(fmaxf(mx, s_nxt[2 * j + 1]), s_nxt[2 * j + 2]);
-            else mx = fmaxf(mx, s_nxt[15]);
+            if (j == 0) mx = vmax3(s_nxt[0], s_nxt[1], s_nxt[2]);
+            else if (j < 7) mx = vmax3(mx, s_nxt[2 * j + 1], s_nxt[2 * j + 2]);
+            else mx = vmax(mx, s_nxt[15]);
         };
         auto unit_step = [&](auto unit) {
             constexpr int U = decltype(unit)::value;
@@ -373,7 +391,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                 for (int j = (U - CH0) * OPS; j < (U - CH0 + 1) * OPS; ++j) max_op(j);
             }
             if constexpr (U == CH0 + NCH) {
-                const float m = fmaxf(mx, other_half(mx)) * c;    // c >= 0
+                const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
                 // The reference maximum only moves when the true one has outgrown it by more than
                 // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32 rows per
                 // wavefront SOME row sets a new maximum in most blocks, and following every one would
@@ -384,8 +402,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             constexpr int NP = 2 * IPW, GAP = NU / NP;
             if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
                 constexpr int P = U / GAP;
-                if (P < IPW ? kb + KAHEAD < nblk : kb + VAHEAD < nblk)
-                    issue_piece(P / IPW, P < IPW ? kb + KAHEAD : kb + VAHEAD, P % IPW);
+                constexpr int W = P / IPW, AHEAD = W ? VAHEAD : KAHEAD;
+                issue_piece(W, kb + AHEAD, P % IPW, (NBUF * W + ((PH + AHEAD) & (NBUF - 1))) * BLKB + (P % IPW) * 1024);
             }
             __builtin_amdgcn_sched_barrier(0);
         };
