@@ -4,14 +4,14 @@
 #include <stdint.h>
 
 #ifndef ATTN_NW
-#define ATTN_NW 4   // wavefronts per workgroup, each owning 32 query rows
+#define ATTN_NW 8   // wavefronts per workgroup, each owning 32 query rows
 #endif
 #define ATTN_BC 32  // keys per inner-loop block
 #ifndef ATTN_MAX_SLACK
 #define ATTN_MAX_SLACK 8.0f  // log2 of the largest softmax weight tolerated before the reference maximum is moved
 #endif
 #ifndef ATTN_NBUF
-#define ATTN_NBUF 4   // LDS buffers per tensor: 4 (two workgroups per CU at D = 128) or 8
+#define ATTN_NBUF 8   // LDS buffers per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
 #endif
 #ifndef ATTN_FETCH
 #define ATTN_FETCH 4  // units between the LDS read of an operand and the matrix instruction that uses it
