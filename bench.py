@@ -20,6 +20,37 @@ import numpy as np
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X published dense matrix peak, TFLOP/s
 
+# HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch, each
+# scaled by what the same counter reads for a plain 1 GiB copy: 2.0 and 1.0), keyed by workload; valid
+# only for the kernel source they were taken with (sha256 over the kernel and its configuration header),
+# otherwise reported as null.
+TRAFFIC = {
+    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 241188 * 2.0, "write_kib": 133154 * 1.0,
+                                      "kernel_sha256": "6000c9ce9650072eab3614b3a8612cc80a8f3331f26f5c8eb266785c112e8653"},
+}
+
+
+def kernel_source_sha256(csrc):
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("attn_fwd_gfx950.hip", "attn_launch.h"):
+        h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload_name):
+    t = TRAFFIC.get(workload_name)
+    if t is None:
+        return None
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2501_08071_amd", "csrc")
+    try:
+        sha = kernel_source_sha256(csrc)
+    except OSError:
+        return None
+    if sha != t["kernel_sha256"]:
+        return None   # the kernel changed since the counters were taken
+    return (t["fetch_kib"] + t["write_kib"]) * 1024.0
+
 
 def cpu_baseline(w, q, k, v, budget_s=15.0):
     """The fp64 oracle as it stands, timed on the host cores over a bounded row sample of the workload."""
@@ -55,6 +86,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cold", action="store_true", help="also time with caches flushed between launches")
     ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run 10 plain device-to-device copies of MIB MiB (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -67,6 +100,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.calibrate_copy:
+        # a plain copy kernel of known size: what FETCH_SIZE / WRITE_SIZE read for it scales those counters
+        n = args.calibrate_copy << 20
+        src = torch.ones(n // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "copies": 10}))
+        return
     w = I.workload(args.workload)
     seed = I.BASE_SEED if args.seed is None else args.seed
     q, k, v = I.gen_inputs(w, seed)
@@ -105,7 +148,9 @@ def main():
                    "scale": w.scale, "seed": seed, "flops_per_step": w.flops,
                    "kernel": P.attn_kernel_name(w.S, w.D, w.dtype, w.causal)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None, "kernel_ms": kern_ms},
+                     "frac": achieved / peak, "traffic": measured_traffic(w.name), "traffic_unit": "bytes/launch",
+                     "algorithmic_bytes": (3 * 2 + 4) * w.B * w.H * w.S * w.D + 4 * w.B * w.H * w.S,
+                     "kernel_ms": kern_ms},
     }
 
     if args.cold:
