@@ -26,7 +26,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X published dense matrix 
 # otherwise reported as null.
 TRAFFIC = {
     "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 241188 * 2.0, "write_kib": 133154 * 1.0,
-                                      "kernel_sha256": "6000c9ce9650072eab3614b3a8612cc80a8f3331f26f5c8eb266785c112e8653"},
+                                      "kernel_sha256": "cc826c67ebcd24abbb8d52d8205705855f0f7784395112dbb68dc2200a2514e4"},
 }
 
 

@@ -10,8 +10,8 @@
 //   K/V stream through LDS in blocks of BC = 32 keys shared by the whole workgroup.
 //
 // K/V movement
-//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), four buffers per tensor,
-//   loads issued three blocks ahead of their use, one barrier per block.  Such a load writes 1 KiB
+//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), ATTN_NBUF buffers per tensor,
+//   loads issued ATTN_NBUF - 1 blocks ahead of their use, one barrier per block.  Such a load writes 1 KiB
 //   of consecutive LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an
 //   XOR swizzle of the 16-byte chunk index within each row, applied on the global-address side.
 //

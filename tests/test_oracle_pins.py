@@ -307,3 +307,35 @@ def test_bad_arguments_are_rejected():
         oracle.attn_oracle(q.astype(np.float32), q, q, False, 1.0, F16)
     with pytest.raises(ValueError):
         oracle.attn_oracle(q, q, q, False, 1.0, 2)
+
+
+# ---- hand-worked fixture ---------------------------------------------------------------
+
+def _read_pow2_fixture():
+    import os
+    rows = {"q": [], "k": [], "v": []}
+    want = {"noncausal": {}, "causal": {}}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "pow2_weights_S4_D2.txt")) as f:
+        for line in f:
+            t = line.split("#")[0].split()
+            if not t:
+                continue
+            if t[0] in rows:
+                rows[t[0]].append([float(x) for x in t[1:]])
+            else:
+                want[t[0]][int(t[1])] = ([int(t[2]), int(t[3])], int(t[4]))
+    return rows, want
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("causal", [False, True])
+def test_hand_worked_rational_weights(causal, dtype):
+    """Integer logits times ln 2 give power-of-two weights; expected values were worked out by hand."""
+    rows, want = _read_pow2_fixture()
+    q, k, v = (bits(np.array(rows[n], np.float32)[None, None], dtype) for n in "qkv")
+    scale = math.log(2.0)
+    o, lse = oracle.attn_oracle(q, k, v, causal, scale, dtype)
+    # the oracle takes scale as fp32: ln 2 rounded to fp32 is off by 1.5e-8 relative, logits are <= 3
+    for i, (num, den) in want["causal" if causal else "noncausal"].items():
+        assert np.abs(o[0, 0, i] - np.array(num) / den).max() < 1e-6
+        assert abs(lse[0, 0, i] - math.log(den)) < 1e-6
