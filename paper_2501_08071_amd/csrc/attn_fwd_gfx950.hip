@@ -301,8 +301,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
     };
 
+    // first ATTN_FETCH operands of the next slot, read before its barrier (so that the matrix pipe does not
+    // sit idle for an LDS round trip after every barrier)
+    constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
+    u32x4 pre[FETCH];
+
     // Slot k of the pipeline (PH = k % NBUF fixes every LDS offset).  Every wavefront: wait for its own
-    // loads of K(k+1) and V(k-1) (issued NBUF-1 slots ago, so newer ones may stay in flight), barrier.
+    // loads of K(k+2) and V(k-1) (issued NBUF-2 slots ago, so newer ones may stay in flight), barrier.
     // Then one straight line for every wavefront and every block: s_cur holds S(k) on entry, s_nxt
     // receives S(k+1); pf_prv holds the weights of block k-1, pf_cur receives those of block k.  From
     // block kd on the masked logits are first replaced by a huge negative number; past the causal
@@ -311,9 +316,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     auto slot = [&](int kb, auto phase, f32x16& s_cur, f32x16& s_nxt, u32x4 (&pf_prv)[2], u32x4 (&pf_cur)[2]) {
         constexpr int PH = decltype(phase)::value;
         constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
+        constexpr int KB2 = (PH + 2) & (NBUF - 1);         // buffer of K(k+2)
         constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
-        wait_block_loads<(NBUF - 2) * 2 * IPW>();
-        __syncthreads();   // ... landed for everybody; nobody still reads K(k), V(k-2)
+        // Before slot k issues its own loads, 2 (k + NBUF - 1) are out.  In the order of issue K(k+2) is
+        // load number 2 k + 4 when it belongs to the prologue (K(j) is number 2 j there, V(j) number
+        // 2 j + 3) and number 2 k + 3 when a slot issued it; V(k-1) comes before either.
+        wait_block_loads<(2 * NBUF - 6) * IPW>();
+        // ... landed for everybody; nobody still reads K(k), V(k-2).  The bare instruction, not the fenced
+        // barrier: the operand reads issued just above stay in flight across it (they read K(k+2), which
+        // nobody overwrites before this wavefront has used them).
+        asm volatile("s_barrier" ::: "memory");
 
         if (kb >= kd) {
             // A block cut by the causal diagonal or by the end of the sequence: masked logits become
@@ -370,7 +382,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         };
         auto unit_step = [&](auto unit) {
             constexpr int U = decltype(unit)::value;
-            if constexpr (U + ATTN_FETCH < NU) fetch(std::integral_constant<int, U + ATTN_FETCH>{});
+            if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
+            else pre[U + FETCH - NU] = lds_read_b128(kaddr[U + FETCH - NU] + KB2 * BLKB);
             if constexpr (U < KSTEPS) {
                 if constexpr (U == 0) {
 #pragma unroll
@@ -407,10 +420,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
             __builtin_amdgcn_sched_barrier(0);
         };
-        [&]<int... U>(std::integer_sequence<int, U...>) {
-            (fetch(std::integral_constant<int, U>{}), ...);
-        }(std::make_integer_sequence<int, ATTN_FETCH>{});
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < FETCH; ++u) opnd[u] = pre[u];
         [&]<int... U>(std::integer_sequence<int, U...>) {
             (unit_step(std::integral_constant<int, U>{}), ...);
         }(std::make_integer_sequence<int, NU>{});
@@ -426,8 +437,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     u32x4 pf_a[2], pf_b[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) pf_b[tt] = u32x4{0u, 0u, 0u, 0u};
-    // prologue: S(0) and its row maximum
-    wait_block_loads<0>();
+    // prologue: S(0) and its row maximum; only K(0) and K(1), the first two loads, have to be there
+    wait_block_loads<(KAHEAD + VAHEAD - 2) * IPW>();
     __syncthreads();
     {
 #pragma unroll
@@ -442,6 +453,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[r]);
         m_ref = fmaxf(mx, other_half(mx)) * c;   // only used if block 0 goes through the main loop
         m_nxt = m_ref;
+#pragma unroll
+        for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u] + (1 & (NBUF - 1)) * BLKB);
     }
 
     // main loop: one slot per block, up to the last block of the workgroup's last wavefront
