@@ -11,7 +11,7 @@
 //
 // K/V movement
 //   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), ATTN_NBUF buffers per tensor,
-//   loads issued ATTN_NBUF - 1 blocks ahead of their use, one barrier per block.  Such a load writes 1 KiB
+//   loads issued about ATTN_NBUF blocks ahead of their use, one barrier per two blocks.  Such a load writes 1 KiB
 //   of consecutive LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an
 //   XOR swizzle of the 16-byte chunk index within each row, applied on the global-address side.
 //
@@ -140,8 +140,10 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
     constexpr int BC = ATTN_BC;        // keys per block
     constexpr int NBUF = ATTN_NBUF;    // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
-    constexpr int KAHEAD = NBUF;       // slot k issues the load of K(k + KAHEAD) ...
-    constexpr int VAHEAD = NBUF - 2;   // ... and of V(k + VAHEAD); both land NBUF - 1 slots before their use
+    constexpr int BEV = ATTN_BARRIER_EVERY;    // slots per workgroup barrier (1 or 2)
+    static_assert((BEV == 1 || BEV == 2) && ATTN_NBUF % BEV == 0, "barrier period");
+    constexpr int KAHEAD = NBUF - (BEV - 1);   // slot k issues the load of K(k + KAHEAD) ...
+    constexpr int VAHEAD = KAHEAD - 2;         // ... and of V(k + VAHEAD): into buffers last read before the previous barrier
     constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
     constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
     constexpr int ROWB = 2 * D;        // bytes per K/V row
@@ -318,14 +320,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
         constexpr int KB2 = (PH + 2) & (NBUF - 1);         // buffer of K(k+2)
         constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
-        // Before slot k issues its own loads, 2 (k + NBUF - 1) are out.  In the order of issue K(k+2) is
-        // load number 2 k + 4 when it belongs to the prologue (K(j) is number 2 j there, V(j) number
-        // 2 j + 3) and number 2 k + 3 when a slot issued it; V(k-1) comes before either.
-        wait_block_loads<(2 * NBUF - 6) * IPW>();
-        // ... landed for everybody; nobody still reads K(k), V(k-2).  The bare instruction, not the fenced
-        // barrier: the operand reads issued just above stay in flight across it (they read K(k+2), which
-        // nobody overwrites before this wavefront has used them).
-        asm volatile("s_barrier" ::: "memory");
+        // A barrier every BEV slots.  Before slot k issues its own loads, 2 (k + KAHEAD - 1) are out; the
+        // slots up to the next barrier read K(k+2) .. K(k+BEV+1) (the last of them is load number
+        // 2 (k+BEV+1) at most) and V(k-1) .. V(k+BEV-2), which come earlier in the order of issue.
+        if constexpr (PH % BEV == 0) {
+            wait_block_loads<(2 * (KAHEAD - 1) - 2 * (BEV + 1)) * IPW>();
+            // ... landed for everybody; nobody still reads the buffers the next BEV slots load into.  The
+            // bare instruction, not the fenced barrier: the operand reads issued just above stay in flight
+            // across it (they read K(k+2), which nobody overwrites before this wavefront has used them).
+            asm volatile("s_barrier" ::: "memory");
+        }
 
         if (kb >= kd) {
             // A block cut by the causal diagonal or by the end of the sequence: masked logits become

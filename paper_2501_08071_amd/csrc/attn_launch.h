@@ -13,6 +13,9 @@
 #ifndef ATTN_NBUF
 #define ATTN_NBUF 8   // LDS buffers per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
 #endif
+#ifndef ATTN_BARRIER_EVERY
+#define ATTN_BARRIER_EVERY 2  // key blocks per workgroup barrier (1 or 2)
+#endif
 #ifndef ATTN_FETCH
 #define ATTN_FETCH 4  // units between the LDS read of an operand and the matrix instruction that uses it
 #endif
