@@ -430,10 +430,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             (unit_step(std::integral_constant<int, U>{}), ...);
         }(std::make_integer_sequence<int, NU>{});
         // block k is done: its weights were taken against m_ref; everything older against m_run
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
-        l_run = l_run * alpha + psum;
-        if (__builtin_amdgcn_ballot_w64(m_ref != m_run) != 0) rescale_o(alpha);
-        m_run = m_ref;
+        if (__builtin_amdgcn_ballot_w64(m_ref != m_run) != 0) {   // rare after the first blocks
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
+            l_run *= alpha;
+            rescale_o(alpha);
+            m_run = m_ref;
+        }
+        l_run += psum;
         m_ref = m_nxt;
     };
 
