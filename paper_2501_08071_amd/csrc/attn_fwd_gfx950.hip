@@ -255,7 +255,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         for (int r = 0; r < 16; ++r) acc_o[i][r] = 0.f;
     float m_run = -INFINITY;   // reference maximum (base-2 units) everything accumulated so far was taken against
     float l_run = 0.f;         // this lane's share of the running row sum
-    float m_ref, m_nxt;        // main loop: reference maximum of the block in hand / of the next one
+    float m_ref;               // main loop: reference maximum of the block in hand
 
     // ---- per-lane LDS addresses (loop invariant; buffer parts become immediate offsets) ----
     // K operand of step ks: row l32 of the block, source chunk 2 ks + h
@@ -348,12 +348,12 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         }
         // Units 0 .. KSTEPS - 1: S(k+1) = K(k+1).Q^T ; units KSTEPS .. NU - 1: O^T += V(k-1)^T.P(k-1)^T.
         // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction on the
-        // unit's operand, and a share of the vector work: every unit its part of the 16 weights of block
-        // k (their reference maximum m_ref was fixed during the previous slot, so the exponentials start
-        // at once), and, once S(k+1) is complete, the row maximum of block k+1 for the next slot.  The
-        // order written here is the order issued: nothing moves across a unit.
+        // unit's operand, and a share of the vector work: its part of the 16 weights of block k.  Their
+        // reference maximum m_ref is the one everything so far was taken against (so the exponentials
+        // start at once); no row maximum is taken here.  The order written here is the order issued:
+        // nothing moves across a unit.
         f32x16 p;
-        float psum = 0.f, mx = 0.f;
+        float psum = 0.f;
         const float neg_m = -m_ref;
         u32x4 opnd[NU];
         auto fetch = [&](auto unit) {
@@ -376,14 +376,6 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                 asm volatile("" : "+v"(psum));   // add here, under the matrix instruction, not later
             }
         };
-        // row maximum of S(k+1): 8 three-input maxima, spread over the units after its last matrix
-        // instruction (CH0 leaves that instruction time to retire), finished one unit later
-        constexpr int CH0 = KSTEPS + 1, NCH = DB == 4 ? 4 : 2, OPS = 8 / NCH;
-        auto max_op = [&](int j) {
-            if (j == 0) mx = vmax3(s_nxt[0], s_nxt[1], s_nxt[2]);
-            else if (j < 7) mx = vmax3(mx, s_nxt[2 * j + 1], s_nxt[2 * j + 2]);
-            else mx = vmax(mx, s_nxt[15]);
-        };
         auto unit_step = [&](auto unit) {
             constexpr int U = decltype(unit)::value;
             if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
@@ -403,18 +395,6 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #pragma unroll
                 for (int r = lo; r < hi; ++r) weight(r);
             }
-            if constexpr (U >= CH0 && U < CH0 + NCH) {
-#pragma unroll
-                for (int j = (U - CH0) * OPS; j < (U - CH0 + 1) * OPS; ++j) max_op(j);
-            }
-            if constexpr (U == CH0 + NCH) {
-                const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
-                // The reference maximum only moves when the true one has outgrown it by more than
-                // 2^ATTN_MAX_SLACK (weights then stay below that, finite in binary16 too).  With 32 rows per
-                // wavefront SOME row sets a new maximum in most blocks, and following every one would
-                // rescale all accumulators nearly every block.
-                m_nxt = m > m_ref + ATTN_MAX_SLACK ? m : m_ref;
-            }
             // the 2 IPW load instructions of this slot, one per unit, evenly spread
             constexpr int NP = 2 * IPW, GAP = NU / NP;
             if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
@@ -429,6 +409,31 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         [&]<int... U>(std::integer_sequence<int, U...>) {
             (unit_step(std::integral_constant<int, U>{}), ...);
         }(std::make_integer_sequence<int, NU>{});
+        // A weight sum above 2^ATTN_MAX_SLACK (or not a number: a weight overflowed) means that some row's
+        // logits have outgrown the reference by about that much: only then the row maxima of the block are
+        // taken, the references of the rows concerned moved up to them and the block's weights computed
+        // again.  Weights stay below 2^ATTN_MAX_SLACK (finite in binary16 too), and the matrix pipe is not
+        // held up by maxima that, after the first blocks, hardly ever change anything.
+        if (__builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0) {
+            float mx = vmax3(s_cur[0], s_cur[1], s_cur[2]);
+#pragma unroll
+            for (int j = 1; j < 7; ++j) mx = vmax3(mx, s_cur[2 * j + 1], s_cur[2 * j + 2]);
+            mx = vmax(mx, s_cur[15]);
+            const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
+            m_ref = m > m_ref ? m : m_ref;
+            const float nm = -m_ref;
+            psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(fmaf(s_cur[r], c, nm));
+                if (r % 2 == 1) {
+                    const uint32_t w = E::pack2(p[r - 1], p[r]);
+                    pf_cur[r / 8][(r % 8) / 2] = w;
+                    if (DT == 0) psum = E::dot2_ones(w, psum);
+                }
+                if (DT == 1) psum += p[r];
+            }
+        }
         // block k is done: its weights were taken against m_ref; everything older against m_run
         if (__builtin_amdgcn_ballot_w64(m_ref != m_run) != 0) {   // rare after the first blocks
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
@@ -437,7 +442,6 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             m_run = m_ref;
         }
         l_run += psum;
-        m_ref = m_nxt;
     };
 
     f32x16 s_a, s_b;
@@ -458,8 +462,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         float mx = s_a[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[r]);
-        m_ref = fmaxf(mx, other_half(mx)) * c;   // only used if block 0 goes through the main loop
-        m_nxt = m_ref;
+        m_ref = fmaxf(mx, other_half(mx)) * c;   // the first reference: the true maxima of block 0
 #pragma unroll
         for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u] + (1 & (NBUF - 1)) * BLKB);
     }

@@ -8,7 +8,7 @@
 #endif
 #define ATTN_BC 32  // keys per inner-loop block
 #ifndef ATTN_MAX_SLACK
-#define ATTN_MAX_SLACK 8.0f  // log2 of the largest softmax weight tolerated before the reference maximum is moved
+#define ATTN_MAX_SLACK 15.0f  // log2 of the largest sum of 16 softmax weights tolerated before the reference maximum is moved
 #endif
 #ifndef ATTN_NBUF
 #define ATTN_NBUF 8   // LDS buffers per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
