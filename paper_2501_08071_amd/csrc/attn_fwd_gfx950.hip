@@ -140,10 +140,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
     constexpr int BC = ATTN_BC;        // keys per block
     constexpr int NBUF = ATTN_NBUF;    // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
-    constexpr int BEV = ATTN_BARRIER_EVERY;    // slots per workgroup barrier (1 or 2)
+    // Two loop structures (see below): D = 128 alternates matrix and vector phases between two groups
+    // of wavefronts; D = 64, where the vector work outweighs the matrix work, interleaves both in every
+    // wavefront.
+    constexpr bool PP = ATTN_PINGPONG != 0 && D == 128;
+    constexpr int BEV = ATTN_BARRIER_EVERY;    // interleaved loop: slots per workgroup barrier (1 or 2)
     static_assert((BEV == 1 || BEV == 2) && ATTN_NBUF % BEV == 0, "barrier period");
-    constexpr int KAHEAD = NBUF - (BEV - 1);   // slot k issues the load of K(k + KAHEAD) ...
-    constexpr int VAHEAD = KAHEAD - 2;         // ... and of V(k + VAHEAD): into buffers last read before the previous barrier
+    // block k's step issues the load of K(k + KAHEAD) and of V(k + VAHEAD), into buffers nobody reads
+    // any more (last read before the previous barrier, by either group)
+    constexpr int KAHEAD = PP ? NBUF - 1 : NBUF - (BEV - 1);
+    constexpr int VAHEAD = PP ? NBUF - 2 : KAHEAD - 2;
     constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
     constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
     constexpr int ROWB = 2 * D;        // bytes per K/V row
@@ -303,185 +309,321 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
     };
 
-    // first ATTN_FETCH operands of the next slot, read before its barrier (so that the matrix pipe does not
-    // sit idle for an LDS round trip after every barrier)
-    constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
-    u32x4 pre[FETCH];
+    if constexpr (PP) {
+        // first operands of the next matrix phase, read before its barrier
+        constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
+        u32x4 pre[FETCH];
+        f32x16 s;        // S(k): written by M(k), read by V(k)
+        u32x4 pf[2];     // weights of block k-1 (matrix operand layout) for M(k)
 
-    // Slot k of the pipeline (PH = k % NBUF fixes every LDS offset).  Every wavefront: wait for its own
-    // loads of K(k+2) and V(k-1) (issued NBUF-2 slots ago, so newer ones may stay in flight), barrier.
-    // Then one straight line for every wavefront and every block: s_cur holds S(k) on entry, s_nxt
-    // receives S(k+1); pf_prv holds the weights of block k-1, pf_cur receives those of block k.  From
-    // block kd on the masked logits are first replaced by a huge negative number; past the causal
-    // diagonal that is all of them, the weights come out as zeros and the slot changes nothing (the
-    // wavefront would otherwise only wait for the others at the next barrier).
-    auto slot = [&](int kb, auto phase, f32x16& s_cur, f32x16& s_nxt, u32x4 (&pf_prv)[2], u32x4 (&pf_cur)[2]) {
-        constexpr int PH = decltype(phase)::value;
-        constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
-        constexpr int KB2 = (PH + 2) & (NBUF - 1);         // buffer of K(k+2)
-        constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
-        // A barrier every BEV slots.  Before slot k issues its own loads, 2 (k + KAHEAD - 1) are out; the
-        // slots up to the next barrier read K(k+2) .. K(k+BEV+1) (the last of them is load number
-        // 2 (k+BEV+1) at most) and V(k-1) .. V(k+BEV-2), which come earlier in the order of issue.
-        if constexpr (PH % BEV == 0) {
-            wait_block_loads<(2 * (KAHEAD - 1) - 2 * (BEV + 1)) * IPW>();
-            // ... landed for everybody; nobody still reads the buffers the next BEV slots load into.  The
-            // bare instruction, not the fenced barrier: the operand reads issued just above stay in flight
-            // across it (they read K(k+2), which nobody overwrites before this wavefront has used them).
-            asm volatile("s_barrier" ::: "memory");
-        }
-
-        if (kb >= kd) {
-            // A block cut by the causal diagonal or by the end of the sequence: masked logits become
-            // -3e38 (times c >= 1e-30 that is far below any real logit and the weight comes out as an
-            // exact 0), and the reference maximum is taken again, over what is left.
-            const int lim = (CAUSAL ? qrow_ld : S - 1) - kb * BC - 4 * h;
-            float m = -3.0e38f;
+        // Two groups of wavefronts (0 .. NW/2-1 and NW/2 .. NW-1; wavefront w and w + NW/2 share a SIMD) run
+        // the same sequence of phases half a block apart: while one group is in its matrix phase M(k) --
+        // S(k) = K(k).Q^T and O^T += V(k-1)^T.P(k-1)^T, nothing but matrix instructions, their LDS operand reads
+        // and the block loads -- the other is in its vector phase V(k') -- row maximum, weights, row sum --
+        // so the two wavefronts of a SIMD never compete for the same pipe.  A workgroup barrier separates the
+        // phases.
+        auto m_phase = [&](int kb, auto phase) {
+            constexpr int PH = decltype(phase)::value;
+            constexpr int KB = PH;                             // buffer of K(k)
+            constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
+            u32x4 opnd[NU];
+            auto fetch = [&](auto unit) {
+                constexpr int U = decltype(unit)::value;
+                if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
+                else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
+            };
+            auto unit_step = [&](auto unit) {
+                constexpr int U = decltype(unit)::value;
+                if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
+                if constexpr (U < KSTEPS) {
+                    if constexpr (U == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int off = 8 * (r / 4) + (r % 4);
-                s_cur[r] = off > lim ? -3.0e38f : s_cur[r];
-                m = fmaxf(m, s_cur[r]);
-            }
-            m = fmaxf(m, other_half(m)) * c;
-            m_ref = m > m_run + ATTN_MAX_SLACK ? m : m_run;
-        }
-        // Units 0 .. KSTEPS - 1: S(k+1) = K(k+1).Q^T ; units KSTEPS .. NU - 1: O^T += V(k-1)^T.P(k-1)^T.
-        // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction on the
-        // unit's operand, and a share of the vector work: its part of the 16 weights of block k.  Their
-        // reference maximum m_ref is the one everything so far was taken against (so the exponentials
-        // start at once); no row maximum is taken here.  The order written here is the order issued:
-        // nothing moves across a unit.
-        f32x16 p;
-        float psum = 0.f;
-        const float neg_m = -m_ref;
-        u32x4 opnd[NU];
-        auto fetch = [&](auto unit) {
-            constexpr int U = decltype(unit)::value;
-            if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
-            else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
-        };
-        auto weight = [&](int r) {
-            p[r] = __builtin_amdgcn_exp2f(fmaf(s_cur[r], c, neg_m));
-            if (r % 2 == 1) {
-                uint32_t w = E::pack2(p[r - 1], p[r]);
-                asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
-                pf_cur[r / 8][(r % 8) / 2] = w;
-                if (DT == 0) psum = E::dot2_ones(w, psum);
-            }
-            // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
-            // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
-            if (DT == 1) {
-                psum += p[r];
-                asm volatile("" : "+v"(psum));   // add here, under the matrix instruction, not later
-            }
-        };
-        auto unit_step = [&](auto unit) {
-            constexpr int U = decltype(unit)::value;
-            if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
-            else pre[U + FETCH - NU] = lds_read_b128(kaddr[U + FETCH - NU] + KB2 * BLKB);
-            if constexpr (U < KSTEPS) {
-                if constexpr (U == 0) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+                        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+                    }
+                    s = E::mfma(opnd[U], qf[U], s);
+                } else {
+                    constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
+                    acc_o[i] = E::mfma(opnd[U], pf[tt], acc_o[i]);
                 }
-                s_nxt = E::mfma(opnd[U], qf[U], s_nxt);
-            } else {
-                constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
-                acc_o[i] = E::mfma(opnd[U], pf_prv[tt], acc_o[i]);
-            }
-            {
-                constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
+                // the 2 IPW load instructions of this block, evenly spread
+                constexpr int NP = 2 * IPW, GAP = NU / NP;
+                if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
+                    constexpr int P = U / GAP;
+                    constexpr int W = P / IPW, AHEAD = W ? VAHEAD : KAHEAD;
+                    issue_piece(W, kb + AHEAD, P % IPW, (NBUF * W + ((PH + AHEAD) & (NBUF - 1))) * BLKB + (P % IPW) * 1024);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
 #pragma unroll
-                for (int r = lo; r < hi; ++r) weight(r);
+            for (int u = 0; u < FETCH; ++u) opnd[u] = pre[u];
+            [&]<int... U>(std::integer_sequence<int, U...>) {
+                (unit_step(std::integral_constant<int, U>{}), ...);
+            }(std::make_integer_sequence<int, NU>{});
+        };
+        auto v_phase = [&](int kb, auto phase) {
+            constexpr int PH = decltype(phase)::value;
+            constexpr int KB1 = (PH + 1) & (NBUF - 1);   // buffer of K(k+1)
+            if (kb >= kd) {
+                // A block cut by the causal diagonal or by the end of the sequence: masked logits become
+                // -3e38 (times c >= 1e-30 that is far below any real logit and the weight comes out as an
+                // exact 0); past the diagonal that is all of them and the phase changes nothing.
+                const int lim = (CAUSAL ? qrow_ld : S - 1) - kb * BC - 4 * h;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int off = 8 * (r / 4) + (r % 4);
+                    s[r] = off > lim ? -3.0e38f : s[r];
+                }
             }
-            // the 2 IPW load instructions of this slot, one per unit, evenly spread
-            constexpr int NP = 2 * IPW, GAP = NU / NP;
-            if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
-                constexpr int P = U / GAP;
-                constexpr int W = P / IPW, AHEAD = W ? VAHEAD : KAHEAD;
-                issue_piece(W, kb + AHEAD, P % IPW, (NBUF * W + ((PH + AHEAD) & (NBUF - 1))) * BLKB + (P % IPW) * 1024);
+            float psum = 0.f;
+            f32x16 p;
+            auto weights = [&](float nm) {
+                psum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, nm));
+                    if (r % 2 == 1) {
+                        const uint32_t w = E::pack2(p[r - 1], p[r]);
+                        pf[r / 8][(r % 8) / 2] = w;
+                        if (DT == 0) psum = E::dot2_ones(w, psum);
+                    }
+                    if (DT == 1) psum += p[r];
+                }
+            };
+            if (kb != 0) weights(-m_ref);
+            if (kb == 0 || __builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0) {
+                float mx = vmax3(s[0], s[1], s[2]);
+#pragma unroll
+                for (int j = 1; j < 7; ++j) mx = vmax3(mx, s[2 * j + 1], s[2 * j + 2]);
+                mx = vmax(mx, s[15]);
+                const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
+                const float m_new = m > m_ref ? m : m_ref;
+                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                l_run *= alpha;
+                rescale_o(alpha);
+                m_ref = m_new;
+                weights(-m_ref);
             }
+            l_run += psum;
+#pragma unroll
+            for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u] + KB1 * BLKB);
+        };
+
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) pf[tt] = u32x4{0u, 0u, 0u, 0u};
+        m_ref = -INFINITY;
+        const bool grp1 = wave >= NW / 2;
+        // prologue: K(0), the first load, has to be there for the first operand reads
+        wait_block_loads<(KAHEAD + VAHEAD - 1) * IPW>();
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u]);
+        if (grp1) asm volatile("s_barrier" ::: "memory");   // the second group starts half a block late
+
+        // In the order of issue K(j) is load number 2 j (K(0) number 1) and V(j) number 2 j + 3; before M(k),
+        // KAHEAD + VAHEAD + 2 k are out.  Every wavefront makes sure of its own share of K(k+2) and V(k+1)
+        // before the barrier in front of its M(k): that is one block more than it needs itself, for the
+        // other group, whose last such check lies half a block back.
+        auto block = [&](int kb, auto phase) {
+            wait_block_loads<(KAHEAD + VAHEAD - 5) * IPW>();
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            m_phase(kb, phase);
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            v_phase(kb, phase);
             __builtin_amdgcn_sched_barrier(0);
         };
+        for (int k0 = 0; k0 <= last_max; k0 += NBUF) {
+            [&]<int... PH>(std::integer_sequence<int, PH...>) {
+                ((k0 + PH <= last_max ? block(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
+            }(std::make_integer_sequence<int, NBUF>{});
+        }
+        if (!grp1) asm volatile("s_barrier" ::: "memory");   // the first group's last one
+        // The second product of the last block is still open.  Every wavefront made sure of its share of
+        // V(last) two blocks ago at the latest, and has passed a barrier since.
+        pv_plain(pf, last_max & (NBUF - 1));
+        m_run = m_ref;
+    } else {
+        // first ATTN_FETCH operands of the next slot, read before its barrier (so that the matrix pipe does not
+        // sit idle for an LDS round trip after every barrier)
+        constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
+        u32x4 pre[FETCH];
+
+        // Slot k of the pipeline (PH = k % NBUF fixes every LDS offset).  Every wavefront: wait for its own
+        // loads of K(k+2) and V(k-1) (issued NBUF-2 slots ago, so newer ones may stay in flight), barrier.
+        // Then one straight line for every wavefront and every block: s_cur holds S(k) on entry, s_nxt
+        // receives S(k+1); pf_prv holds the weights of block k-1, pf_cur receives those of block k.  From
+        // block kd on the masked logits are first replaced by a huge negative number; past the causal
+        // diagonal that is all of them, the weights come out as zeros and the slot changes nothing (the
+        // wavefront would otherwise only wait for the others at the next barrier).
+        auto slot = [&](int kb, auto phase, f32x16& s_cur, f32x16& s_nxt, u32x4 (&pf_prv)[2], u32x4 (&pf_cur)[2]) {
+            constexpr int PH = decltype(phase)::value;
+            constexpr int KB = (PH + 1) & (NBUF - 1);          // buffer of K(k+1)
+            constexpr int KB2 = (PH + 2) & (NBUF - 1);         // buffer of K(k+2)
+            constexpr int VB = (PH + NBUF - 1) & (NBUF - 1);   // buffer of V(k-1)
+            // A barrier every BEV slots.  Before slot k issues its own loads, 2 (k + KAHEAD - 1) are out; the
+            // slots up to the next barrier read K(k+2) .. K(k+BEV+1) (the last of them is load number
+            // 2 (k+BEV+1) at most) and V(k-1) .. V(k+BEV-2), which come earlier in the order of issue.
+            if constexpr (PH % BEV == 0) {
+                wait_block_loads<(2 * (KAHEAD - 1) - 2 * (BEV + 1)) * IPW>();
+                // ... landed for everybody; nobody still reads the buffers the next BEV slots load into.  The
+                // bare instruction, not the fenced barrier: the operand reads issued just above stay in flight
+                // across it (they read K(k+2), which nobody overwrites before this wavefront has used them).
+                asm volatile("s_barrier" ::: "memory");
+            }
+
+            if (kb >= kd) {
+                // A block cut by the causal diagonal or by the end of the sequence: masked logits become
+                // -3e38 (times c >= 1e-30 that is far below any real logit and the weight comes out as an
+                // exact 0), and the reference maximum is taken again, over what is left.
+                const int lim = (CAUSAL ? qrow_ld : S - 1) - kb * BC - 4 * h;
+                float m = -3.0e38f;
 #pragma unroll
-        for (int u = 0; u < FETCH; ++u) opnd[u] = pre[u];
-        [&]<int... U>(std::integer_sequence<int, U...>) {
-            (unit_step(std::integral_constant<int, U>{}), ...);
-        }(std::make_integer_sequence<int, NU>{});
-        // A weight sum above 2^ATTN_MAX_SLACK (or not a number: a weight overflowed) means that some row's
-        // logits have outgrown the reference by about that much: only then the row maxima of the block are
-        // taken, the references of the rows concerned moved up to them and the block's weights computed
-        // again.  Weights stay below 2^ATTN_MAX_SLACK (finite in binary16 too), and the matrix pipe is not
-        // held up by maxima that, after the first blocks, hardly ever change anything.
-        if (__builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0) {
-            float mx = vmax3(s_cur[0], s_cur[1], s_cur[2]);
-#pragma unroll
-            for (int j = 1; j < 7; ++j) mx = vmax3(mx, s_cur[2 * j + 1], s_cur[2 * j + 2]);
-            mx = vmax(mx, s_cur[15]);
-            const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
-            m_ref = m > m_ref ? m : m_ref;
-            const float nm = -m_ref;
-            psum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                p[r] = __builtin_amdgcn_exp2f(fmaf(s_cur[r], c, nm));
+                for (int r = 0; r < 16; ++r) {
+                    const int off = 8 * (r / 4) + (r % 4);
+                    s_cur[r] = off > lim ? -3.0e38f : s_cur[r];
+                    m = fmaxf(m, s_cur[r]);
+                }
+                m = fmaxf(m, other_half(m)) * c;
+                m_ref = m > m_run + ATTN_MAX_SLACK ? m : m_run;
+            }
+            // Units 0 .. KSTEPS - 1: S(k+1) = K(k+1).Q^T ; units KSTEPS .. NU - 1: O^T += V(k-1)^T.P(k-1)^T.
+            // A unit is: the LDS read of the operand ATTN_FETCH units ahead, one matrix instruction on the
+            // unit's operand, and a share of the vector work: its part of the 16 weights of block k.  Their
+            // reference maximum m_ref is the one everything so far was taken against (so the exponentials
+            // start at once); no row maximum is taken here.  The order written here is the order issued:
+            // nothing moves across a unit.
+            f32x16 p;
+            float psum = 0.f;
+            const float neg_m = -m_ref;
+            u32x4 opnd[NU];
+            auto fetch = [&](auto unit) {
+                constexpr int U = decltype(unit)::value;
+                if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
+                else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
+            };
+            auto weight = [&](int r) {
+                p[r] = __builtin_amdgcn_exp2f(fmaf(s_cur[r], c, neg_m));
                 if (r % 2 == 1) {
-                    const uint32_t w = E::pack2(p[r - 1], p[r]);
+                    uint32_t w = E::pack2(p[r - 1], p[r]);
+                    asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
                     pf_cur[r / 8][(r % 8) / 2] = w;
                     if (DT == 0) psum = E::dot2_ones(w, psum);
                 }
-                if (DT == 1) psum += p[r];
+                // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
+                // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
+                if (DT == 1) {
+                    psum += p[r];
+                    asm volatile("" : "+v"(psum));   // add here, under the matrix instruction, not later
+                }
+            };
+            auto unit_step = [&](auto unit) {
+                constexpr int U = decltype(unit)::value;
+                if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
+                else pre[U + FETCH - NU] = lds_read_b128(kaddr[U + FETCH - NU] + KB2 * BLKB);
+                if constexpr (U < KSTEPS) {
+                    if constexpr (U == 0) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) s_nxt[r] = 0.f;
+                    }
+                    s_nxt = E::mfma(opnd[U], qf[U], s_nxt);
+                } else {
+                    constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
+                    acc_o[i] = E::mfma(opnd[U], pf_prv[tt], acc_o[i]);
+                }
+                {
+                    constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
+#pragma unroll
+                    for (int r = lo; r < hi; ++r) weight(r);
+                }
+                // the 2 IPW load instructions of this slot, one per unit, evenly spread
+                constexpr int NP = 2 * IPW, GAP = NU / NP;
+                if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
+                    constexpr int P = U / GAP;
+                    constexpr int W = P / IPW, AHEAD = W ? VAHEAD : KAHEAD;
+                    issue_piece(W, kb + AHEAD, P % IPW, (NBUF * W + ((PH + AHEAD) & (NBUF - 1))) * BLKB + (P % IPW) * 1024);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            };
+#pragma unroll
+            for (int u = 0; u < FETCH; ++u) opnd[u] = pre[u];
+            [&]<int... U>(std::integer_sequence<int, U...>) {
+                (unit_step(std::integral_constant<int, U>{}), ...);
+            }(std::make_integer_sequence<int, NU>{});
+            // A weight sum above 2^ATTN_MAX_SLACK (or not a number: a weight overflowed) means that some row's
+            // logits have outgrown the reference by about that much: only then the row maxima of the block are
+            // taken, the references of the rows concerned moved up to them and the block's weights computed
+            // again.  Weights stay below 2^ATTN_MAX_SLACK (finite in binary16 too), and the matrix pipe is not
+            // held up by maxima that, after the first blocks, hardly ever change anything.
+            if (__builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0) {
+                float mx = vmax3(s_cur[0], s_cur[1], s_cur[2]);
+#pragma unroll
+                for (int j = 1; j < 7; ++j) mx = vmax3(mx, s_cur[2 * j + 1], s_cur[2 * j + 2]);
+                mx = vmax(mx, s_cur[15]);
+                const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
+                m_ref = m > m_ref ? m : m_ref;
+                const float nm = -m_ref;
+                psum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    p[r] = __builtin_amdgcn_exp2f(fmaf(s_cur[r], c, nm));
+                    if (r % 2 == 1) {
+                        const uint32_t w = E::pack2(p[r - 1], p[r]);
+                        pf_cur[r / 8][(r % 8) / 2] = w;
+                        if (DT == 0) psum = E::dot2_ones(w, psum);
+                    }
+                    if (DT == 1) psum += p[r];
+                }
             }
-        }
-        // block k is done: its weights were taken against m_ref; everything older against m_run
-        if (__builtin_amdgcn_ballot_w64(m_ref != m_run) != 0) {   // rare after the first blocks
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
-            l_run *= alpha;
-            rescale_o(alpha);
-            m_run = m_ref;
-        }
-        l_run += psum;
-    };
+            // block k is done: its weights were taken against m_ref; everything older against m_run
+            if (__builtin_amdgcn_ballot_w64(m_ref != m_run) != 0) {   // rare after the first blocks
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);
+                l_run *= alpha;
+                rescale_o(alpha);
+                m_run = m_ref;
+            }
+            l_run += psum;
+        };
 
-    f32x16 s_a, s_b;
-    u32x4 pf_a[2], pf_b[2];
+        f32x16 s_a, s_b;
+        u32x4 pf_a[2], pf_b[2];
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) pf_b[tt] = u32x4{0u, 0u, 0u, 0u};
-    // prologue: S(0) and its row maximum; only K(0) and K(1), the first two loads, have to be there
-    wait_block_loads<(KAHEAD + VAHEAD - 2) * IPW>();
-    __syncthreads();
-    {
+        for (int tt = 0; tt < 2; ++tt) pf_b[tt] = u32x4{0u, 0u, 0u, 0u};
+        // prologue: S(0) and its row maximum; only K(0) and K(1), the first two loads, have to be there
+        wait_block_loads<(KAHEAD + VAHEAD - 2) * IPW>();
+        __syncthreads();
+        {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
+            for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            s_a = E::mfma(lds_read_b128(kaddr[ks]), qf[ks], s_a);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                s_a = E::mfma(lds_read_b128(kaddr[ks]), qf[ks], s_a);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            float mx = s_a[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[r]);
+            m_ref = fmaxf(mx, other_half(mx)) * c;   // the first reference: the true maxima of block 0
+#pragma unroll
+            for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u] + (1 & (NBUF - 1)) * BLKB);
         }
-        float mx = s_a[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_a[r]);
-        m_ref = fmaxf(mx, other_half(mx)) * c;   // the first reference: the true maxima of block 0
-#pragma unroll
-        for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u] + (1 & (NBUF - 1)) * BLKB);
-    }
 
-    // main loop: one slot per block, up to the last block of the workgroup's last wavefront
-    for (int k0 = 0; k0 <= last_max; k0 += NBUF) {
-        [&]<int... PH>(std::integer_sequence<int, PH...>) {
-            ((k0 + PH <= last_max
-                  ? (PH % 2 == 0 ? slot(k0 + PH, std::integral_constant<int, PH>{}, s_a, s_b, pf_b, pf_a)
-                                 : slot(k0 + PH, std::integral_constant<int, PH>{}, s_b, s_a, pf_a, pf_b))
-                  : (void)0),
-             ...);
-        }(std::make_integer_sequence<int, NBUF>{});
+        // main loop: one slot per block, up to the last block of the workgroup's last wavefront
+        for (int k0 = 0; k0 <= last_max; k0 += NBUF) {
+            [&]<int... PH>(std::integer_sequence<int, PH...>) {
+                ((k0 + PH <= last_max
+                      ? (PH % 2 == 0 ? slot(k0 + PH, std::integral_constant<int, PH>{}, s_a, s_b, pf_b, pf_a)
+                                     : slot(k0 + PH, std::integral_constant<int, PH>{}, s_b, s_a, pf_a, pf_b))
+                      : (void)0),
+                 ...);
+            }(std::make_integer_sequence<int, NBUF>{});
+        }
+        // The second product of the last block is still open; its weights sit in pf_a / pf_b by parity.
+        wait_block_loads<0>();
+        __syncthreads();
+        if (last_max & 1) pv_plain(pf_b, last_max & (NBUF - 1));
+        else pv_plain(pf_a, last_max & (NBUF - 1));
     }
-    // The second product of the last block is still open; its weights sit in pf_a / pf_b by parity.
-    wait_block_loads<0>();
-    __syncthreads();
-    if (last_max & 1) pv_plain(pf_b, last_max & (NBUF - 1));
-    else pv_plain(pf_a, last_max & (NBUF - 1));
 
     // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
     const float l_tot = l_run + other_half(l_run);

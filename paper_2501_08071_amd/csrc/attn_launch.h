@@ -16,6 +16,9 @@
 #ifndef ATTN_BARRIER_EVERY
 #define ATTN_BARRIER_EVERY 2  // key blocks per workgroup barrier (1 or 2)
 #endif
+#ifndef ATTN_PINGPONG
+#define ATTN_PINGPONG 1  // D = 128: alternate matrix and vector phases between two groups of wavefronts
+#endif
 #ifndef ATTN_FETCH
 #define ATTN_FETCH 4  // units between the LDS read of an operand and the matrix instruction that uses it
 #endif
