@@ -59,6 +59,35 @@ def test_huge_logits_do_not_overflow():
     check_full(q, k, v, BF16, False, 1.0, "huge logits")
 
 
+def _trend_inputs(S, D, dtype, kind, seed):
+    """Keys whose logits follow a trend along the sequence: the running maximum of a row keeps moving
+    (rising), never moves after the first block (falling), or jumps once, late, in some rows (spike)."""
+    rng = np.random.default_rng(seed)
+    qf = rng.standard_normal((1, 2, S, D)).astype(np.float32)
+    kf = rng.standard_normal((1, 2, S, D)).astype(np.float32) * 0.25
+    vf = rng.standard_normal((1, 2, S, D)).astype(np.float32)
+    u = np.ones(D, np.float32) / math.sqrt(D)
+    qf += 4.0 * u                                   # every query has a component along u ...
+    pos = np.arange(S, dtype=np.float32)[None, None, :, None]
+    if kind == "rising":
+        kf += (pos / 8.0) * u                       # ... so q.k grows by about 0.5 per key
+    elif kind == "falling":
+        kf -= (pos / 8.0) * u
+    else:
+        kf[..., S - 37, :] += 60.0 * u              # one key far above all the others, near the end
+    return tuple(I.to_bits(t, dtype) for t in (qf, kf, vf))
+
+
+@pytest.mark.parametrize("kind", ["rising", "falling", "spike"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype,D", [(F16, 64), (BF16, 128), (F16, 128), (BF16, 64)])
+def test_moving_reference_maximum(dtype, D, causal, kind):
+    """The kernel takes row maxima only when a block's weight sum overflows a threshold: drive that path
+    many times (rising), never (falling), and once with a jump of many orders of magnitude (spike)."""
+    q, k, v = _trend_inputs(421, D, dtype, kind, seed=7)
+    check_full(q, k, v, dtype, causal, 1.0, f"{kind} logits D={D}")
+
+
 def test_closed_forms_on_gpu():
     S, D = 300, 64
     q, k, v = I.gen_tensors(1, 2, S, D, F16, workload_id=203)
