@@ -433,10 +433,25 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             v_phase(kb, phase);
             __builtin_amdgcn_sched_barrier(0);
         };
-        for (int k0 = 0; k0 <= last_max; k0 += NBUF) {
+        // Under the causal mask a wavefront is done after M(kd+1), which adds the second product of its
+        // diagonal block kd: every later block of the workgroup is masked entirely for it (and V(kd+1)
+        // has left all-zero weights for the closing product after the loop).  From then on it only
+        // issues its share of the block loads and keeps the barriers.
+        const int last_w = CAUSAL && kd + 1 < last_max ? kd + 1 : last_max;
+        for (int k0 = 0; k0 <= last_w; k0 += NBUF) {
             [&]<int... PH>(std::integer_sequence<int, PH...>) {
-                ((k0 + PH <= last_max ? block(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
+                ((k0 + PH <= last_w ? block(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
             }(std::make_integer_sequence<int, NBUF>{});
+        }
+        for (int kb = last_w + 1; kb <= last_max; ++kb) {
+            wait_block_loads<(KAHEAD + VAHEAD - 5) * IPW>();
+            asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+            for (int P = 0; P < 2 * IPW; ++P) {
+                const int W = P / IPW, AHEAD = W ? VAHEAD : KAHEAD;
+                issue_piece(W, kb + AHEAD, P % IPW, (NBUF * W + ((kb + AHEAD) & (NBUF - 1))) * BLKB + (P % IPW) * 1024);
+            }
+            asm volatile("s_barrier" ::: "memory");
         }
         if (!grp1) asm volatile("s_barrier" ::: "memory");   // the first group's last one
         // The second product of the last block is still open.  Every wavefront made sure of its share of
