@@ -150,6 +150,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // any more (last read before the previous barrier, by either group)
     constexpr int KAHEAD = PP ? NBUF - 1 : NBUF - (BEV - 1);
     constexpr int VAHEAD = PP ? NBUF - 2 : KAHEAD - 2;
+    static_assert(PP ? KAHEAD + VAHEAD >= 5 : KAHEAD - 1 >= BEV + 1, "too few buffers for the loads that have to be in flight");
     constexpr int KSTEPS = D / 16;     // contraction steps of Q.K^T
     constexpr int DB = D / 32;         // 32-wide blocks of the head dimension
     constexpr int ROWB = 2 * D;        // bytes per K/V row

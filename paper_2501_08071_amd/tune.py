@@ -1,0 +1,223 @@
+"""The schedule game, deterministic: a hill climb over the kernel's compile-time schedule knobs.
+
+The paper improves a fixed kernel by moving instructions and rewarding each move with the throughput
+it gains (Section 3: state = the current schedule, action = one move, reward
+R = (T_prev - T) / T_0 * 100 with T_0 the time of the initial schedule; Sections 3.6 and 5.1: a time is
+the mean of 100 launches after 100 warm-up launches; Section 4: the best schedule found is cached per
+GPU type and kernel configuration).  The paper searches with a reinforcement-learning agent over
+single-instruction moves of NVIDIA machine code.  Here the moves are the schedule decisions this kernel
+exposes at compile time -- how the matrix and vector work of the two wavefronts of a SIMD share the
+time, how often the workgroup synchronises, how far ahead operands and blocks are requested -- the
+search is exhaustive over the neighbours of the current state and greedy, so it is reproducible, and
+every candidate's output is compared with that of the shipped library on the same inputs before it is
+timed (the paper validates mutated schedules the same way, against the original schedule's output on
+random inputs, Section 3.7).
+
+  python -m paper_2501_08071_amd.tune build            compile every state of the grid (CPU, no GPU needed)
+  python -m paper_2501_08071_amd.tune play [-w 3]      play the game on the GPU, print the trajectory,
+                                                       store the result in tune_cache.json
+
+The game logic (`play_game`) is independent of the GPU: it takes a function state -> seconds.
+"""
+from __future__ import annotations
+
+import argparse
+import itertools
+import json
+import os
+import sys
+from typing import Callable, Dict, List, Sequence, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+VARIANTS = os.path.join(HERE, "variants")
+CACHE = os.path.join(HERE, "tune_cache.json")
+
+# knob -> (macro, ordered values).  A move changes one knob to a neighbouring value.
+KNOBS: Dict[str, Tuple[str, Tuple[int, ...]]] = {
+    "pingpong": ("ATTN_PINGPONG", (0, 1)),          # D = 128: alternate matrix / vector phases between wavefront groups
+    "barrier_every": ("ATTN_BARRIER_EVERY", (1, 2)),  # interleaved loop: key blocks per workgroup barrier
+    "fetch": ("ATTN_FETCH", (2, 4, 6)),             # matrix instructions between an LDS operand read and its use
+    "nbuf": ("ATTN_NBUF", (4, 8)),                  # LDS buffers per tensor = how far ahead blocks are requested
+}
+State = Tuple[int, ...]                             # one value per knob, in KNOBS order
+START: State = (0, 1, 2, 4)                         # the plainest schedule: everything interleaved, nothing far ahead
+NOISE_PCT = 1.0                                     # two measurements of one schedule agree within about 1 % (Section 3.6)
+
+
+def valid(s: State) -> bool:
+    """Four buffers cannot hold what two key blocks between barriers need in flight."""
+    d = dict(zip(KNOBS, s))
+    return not (d["nbuf"] == 4 and d["barrier_every"] == 2)
+
+
+def all_states() -> List[State]:
+    return [s for s in itertools.product(*(v for _, v in KNOBS.values())) if valid(s)]
+
+
+def neighbours(s: State) -> List[State]:
+    out = []
+    for i, (_, vals) in enumerate(KNOBS.values()):
+        j = vals.index(s[i])
+        for jj in (j - 1, j + 1):
+            if 0 <= jj < len(vals):
+                n = s[:i] + (vals[jj],) + s[i + 1:]
+                if valid(n):
+                    out.append(n)
+    return out
+
+
+def state_name(s: State) -> str:
+    return "_".join(f"{k}{v}" for k, v in zip(KNOBS, s))
+
+
+def state_flags(s: State) -> List[str]:
+    return [f"-D{macro}={v}" for (macro, _), v in zip(KNOBS.values(), s)]
+
+
+def reward(t_prev: float, t: float, t0: float) -> float:
+    """Section 3.4: the gain of a move in percent of the initial schedule's time."""
+    return (t_prev - t) / t0 * 100.0
+
+
+def play_game(measure: Callable[[State], float], start: State = START, noise_pct: float = NOISE_PCT,
+              max_moves: int = 16) -> dict:
+    """Greedy, exhaustive-neighbourhood hill climb.  `measure(state)` returns seconds (or +inf for a state
+    that failed its check).  Every state is measured at most once.  Returns the trajectory."""
+    seen: Dict[State, float] = {}
+
+    def t_of(s: State) -> float:
+        if s not in seen:
+            seen[s] = float(measure(s))
+        return seen[s]
+
+    cur, t0 = start, t_of(start)
+    if not t0 < float("inf"):
+        raise RuntimeError("the initial schedule failed")
+    t_cur, moves = t0, []
+    for _ in range(max_moves):
+        cands = sorted(((t_of(n), n) for n in neighbours(cur)), key=lambda x: (x[0], x[1]))
+        t_best, best = cands[0]
+        r = reward(t_cur, t_best, t0)
+        if r <= noise_pct:      # no move gains more than the measurement noise: the game ends
+            break
+        moves.append({"from": state_name(cur), "to": state_name(best), "t": t_best, "reward": r})
+        cur, t_cur = best, t_best
+    return {"start": state_name(start), "t0": t0, "moves": moves, "final": state_name(cur), "t_final": t_cur,
+            "total_reward": reward(t0, t_cur, t0), "speedup": t0 / t_cur, "measured": {state_name(k): v for k, v in seen.items()}}
+
+
+# ---- building and measuring the states -----------------------------------------------------------------
+
+def variant_path(s: State) -> str:
+    return os.path.join(VARIANTS, f"libattn_{state_name(s)}.so")
+
+
+def build_grid(states: Sequence[State] = None, jobs: int = 4) -> None:
+    from concurrent.futures import ThreadPoolExecutor
+    from . import build as B
+    os.makedirs(VARIANTS, exist_ok=True)
+    states = list(states or all_states())
+
+    def one(s):
+        B.build_lib(extra_flags=state_flags(s), out=variant_path(s))
+        return state_name(s)
+
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        for name in ex.map(one, states):
+            print("built", name, flush=True)
+
+
+def gpu_measure(workload_id: int, warmup: int = 100, steps: int = 100) -> Callable[[State], float]:
+    """Timer for one workload: loads the state's library, compares its output with the shipped library's on
+    the same inputs (max-abs 2e-2, mean-abs 2e-3, logsumexp 1e-3: the bar the shipped library itself meets
+    against the CPU reference in the test-suite), then times it with the paper's protocol."""
+    import ctypes
+    import numpy as np
+    import torch
+    from . import build as B
+    from . import inputs as I
+
+    w = I.workload(workload_id)
+    q, k, v = I.gen_inputs(w)
+    tdt = torch.float16 if w.dtype == I.F16 else torch.bfloat16
+    dq, dk, dv = (torch.from_numpy(t.view(np.int16)).cuda().view(tdt) for t in (q, k, v))
+    o = torch.empty((w.B, w.H, w.S, w.D), dtype=torch.float32, device="cuda")
+    lse = torch.empty((w.B, w.H, w.S), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    vp = ctypes.c_void_p
+
+    def load(path):
+        lib = ctypes.CDLL(path)
+        lib.attn_fwd.argtypes = [vp] * 5 + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int, vp]
+
+        def call():
+            rc = lib.attn_fwd(dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), o.data_ptr(), lse.data_ptr(),
+                              w.B, w.H, w.S, w.D, int(w.causal), w.scale, w.dtype, stream)
+            if rc != 0:
+                raise RuntimeError(f"attn_fwd returned {rc} ({path})")
+        return call
+
+    if not os.path.exists(B.LIB):
+        raise FileNotFoundError(f"{B.LIB}: build the library first")
+    load(B.LIB)()
+    torch.cuda.synchronize()
+    o_ref, l_ref = o.clone(), lse.clone()
+
+    def measure(s: State) -> float:
+        path = variant_path(s)
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path}: run `python -m paper_2501_08071_amd.tune build` first")
+        call = load(path)
+        o.zero_(); lse.zero_()
+        call(); torch.cuda.synchronize()
+        d = (o - o_ref).abs()
+        dl = (lse - l_ref).abs() / l_ref.abs().clamp(min=1.0)
+        ok = bool(torch.isfinite(o).all()) and d.max().item() <= 2e-2 and d.mean().item() <= 2e-3 and dl.max().item() <= 1e-3
+        if not ok:
+            return float("inf")     # a schedule that changes the result is not a schedule
+        for _ in range(warmup):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps * 1e-3
+
+    return measure
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    b = sub.add_parser("build"); b.add_argument("-j", "--jobs", type=int, default=4)
+    p = sub.add_parser("play")
+    p.add_argument("-w", "--workload", type=int, default=3)
+    p.add_argument("--warmup", type=int, default=100); p.add_argument("--steps", type=int, default=100)
+    args = ap.parse_args(argv)
+    if args.cmd == "build":
+        build_grid(jobs=args.jobs)
+        return 0
+    import torch
+    from . import inputs as I
+    if not torch.cuda.is_available():
+        print("tune play: no GPU visible", file=sys.stderr)
+        return 1
+    w = I.workload(args.workload)
+    res = play_game(gpu_measure(args.workload, args.warmup, args.steps))
+    flops = w.flops
+    print(f"workload {w.name} on {torch.cuda.get_device_name(0)}")
+    print(f"  start  {res['start']:44s} {res['t0']*1e3:8.4f} ms  {flops/res['t0']/1e12:7.1f} TFLOP/s")
+    for m in res["moves"]:
+        print(f"  move   {m['to']:44s} {m['t']*1e3:8.4f} ms  {flops/m['t']/1e12:7.1f} TFLOP/s  reward {m['reward']:+6.2f}")
+    print(f"  final  {res['final']:44s} {res['t_final']*1e3:8.4f} ms  total reward {res['total_reward']:+.2f}  speed-up {res['speedup']:.3f}x"
+          f"  ({len(res['measured'])} of {len(all_states())} schedules measured)")
+    cache = json.load(open(CACHE)) if os.path.exists(CACHE) else {}
+    cache[f"{torch.cuda.get_device_name(0)}|{w.name}"] = res
+    json.dump(cache, open(CACHE, "w"), indent=1, sort_keys=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,35 @@
+"""Every schedule variant the tuner can visit must compute attention: parity against the oracle."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_08071_amd import inputs as I
+from paper_2501_08071_amd import tune
+from parity import assert_parity, to_device
+
+pytestmark = pytest.mark.gpu
+BUILT = [s for s in tune.all_states() if os.path.exists(tune.variant_path(s))]
+
+
+@pytest.mark.skipif(not BUILT, reason="schedule variants not built (python -m paper_2501_08071_amd.tune build)")
+@pytest.mark.parametrize("state", BUILT, ids=tune.state_name)
+def test_variant_parity(state):
+    lib = ctypes.CDLL(tune.variant_path(state))
+    vp = ctypes.c_void_p
+    lib.attn_fwd.argtypes = [vp] * 5 + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int, vp]
+    for (B, H, S, D, dtype, causal) in [(1, 2, 300, 128, I.BF16, True), (1, 2, 517, 64, I.F16, False), (1, 1, 640, 128, I.F16, False)]:
+        q, k, v = I.gen_tensors(B, H, S, D, dtype, workload_id=300 + D)
+        dq, dk, dv = (to_device(t, dtype) for t in (q, k, v))
+        o = torch.empty((B, H, S, D), dtype=torch.float32, device="cuda")
+        lse = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+        scale = 1.0 / np.sqrt(D)
+        rc = lib.attn_fwd(dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, S, D, int(causal),
+                          scale, dtype, None)
+        assert rc == 0
+        torch.cuda.synchronize()
+        o_ref, l_ref = oracle.attn_oracle(q, k, v, causal, scale, dtype)
+        assert_parity(o.cpu().numpy(), lse.cpu().numpy(), o_ref, l_ref, f"{tune.state_name(state)} S={S} D={D}")
