@@ -66,6 +66,15 @@ typedef enum {
 int attn_fwd(const void *q, const void *k, const void *v, float *o, float *lse,
              int B, int H, int S, int D, int causal, float scale, int dtype, void *stream);
 
+/*
+ * The same operation with O written in the type of q, k and v (Table 2 gives the kernel's inputs as
+ * fp16 tensors; a layer that feeds the next one in half precision wants O that way), rounded to
+ * nearest even from the fp32 result.  `o` is [B,H,S,D] contiguous in `dtype`; lse stays fp32.  Every
+ * other argument, the ownership and error rules are those of attn_fwd; both share one kernel.
+ */
+int attn_fwd_o16(const void *q, const void *k, const void *v, void *o, float *lse,
+                 int B, int H, int S, int D, int causal, float scale, int dtype, void *stream);
+
 /* 1 if attn_fwd has a kernel instance for this request, else 0 (no HIP call). */
 int attn_supported(int S, int D, int dtype, int causal);
 

@@ -6,11 +6,11 @@ imported on a machine without the HIP library.
 """
 from . import inputs  # noqa: F401
 
-__all__ = ["inputs", "attn_fwd", "attn_supported", "attn_status_str", "lib"]
+__all__ = ["inputs", "attn_fwd", "attn_fwd_o16", "attn_supported", "attn_status_str", "lib"]
 
 
 def __getattr__(name):
-    if name in ("attn_fwd", "attn_fwd_raw", "attn_supported", "attn_status_str", "attn_kernel_name",
+    if name in ("attn_fwd", "attn_fwd_raw", "attn_fwd_o16", "attn_fwd_o16_raw", "attn_supported", "attn_status_str", "attn_kernel_name",
                 "attn_tile_rows", "attn_tile_keys", "lib", "AttnError", "F16", "BF16"):
         from . import binding
         return getattr(binding, name)

@@ -35,6 +35,8 @@ def _load() -> ctypes.CDLL:
     vp = ctypes.c_void_p
     lib.attn_fwd.argtypes = [vp, vp, vp, vp, vp] + [ctypes.c_int] * 5 + [ctypes.c_float, ctypes.c_int, vp]
     lib.attn_fwd.restype = ctypes.c_int
+    lib.attn_fwd_o16.argtypes = lib.attn_fwd.argtypes
+    lib.attn_fwd_o16.restype = ctypes.c_int
     lib.attn_supported.argtypes = [ctypes.c_int] * 4
     lib.attn_supported.restype = ctypes.c_int
     lib.attn_status_str.argtypes = [ctypes.c_int]
@@ -78,7 +80,20 @@ def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale,
                             stream or None))
 
 
-def attn_fwd(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None, want_lse: bool = True):
+def attn_fwd_o16_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale, dtype, stream) -> int:
+    """attn_fwd_o16 as is: device addresses as ints (0 = NULL), returns the status."""
+    return int(lib.attn_fwd_o16(q_ptr or None, k_ptr or None, v_ptr or None, o_ptr or None, lse_ptr or None,
+                                int(B), int(H), int(S), int(D), int(causal), float(scale), int(dtype),
+                                stream or None))
+
+
+def attn_fwd_o16(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None, want_lse: bool = True):
+    """attn_fwd_o16 on torch device tensors: as attn_fwd, with o in the dtype of q, k, v."""
+    return attn_fwd(q, k, v, causal, scale, o=o, lse=lse, stream=stream, want_lse=want_lse, _o16=True)
+
+
+def attn_fwd(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None, want_lse: bool = True,
+             _o16: bool = False):
     """attn_fwd on torch device tensors.
 
     q, k, v : [B,H,S,D] contiguous torch.float16 or torch.bfloat16 tensors on the GPU.
@@ -100,17 +115,19 @@ def attn_fwd(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None,
         if not t.is_cuda or not t.is_contiguous():
             raise ValueError("q, k, v must be contiguous device tensors")
     B, H, S, D = q.shape
+    odt = q.dtype if _o16 else torch.float32
     if o is None:
-        o = torch.empty((B, H, S, D), dtype=torch.float32, device=q.device)
+        o = torch.empty((B, H, S, D), dtype=odt, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty((B, H, S), dtype=torch.float32, device=q.device)
-    for t, shp in ((o, (B, H, S, D)), (lse, (B, H, S))):
-        if t is not None and (t.dtype != torch.float32 or tuple(t.shape) != shp or not t.is_contiguous()
-                              or not t.is_cuda):
-            raise ValueError("o / lse must be contiguous fp32 device tensors of shape [B,H,S,D] / [B,H,S]")
+    for t, shp, dt in ((o, (B, H, S, D), odt), (lse, (B, H, S), torch.float32)):
+        if t is not None and (t.dtype != dt or tuple(t.shape) != shp or not t.is_contiguous() or not t.is_cuda):
+            raise ValueError("o / lse must be contiguous device tensors of shape [B,H,S,D] / [B,H,S] (lse fp32; o fp32, "
+                             "or the input dtype for attn_fwd_o16)")
     st = (stream or torch.cuda.current_stream(q.device)).cuda_stream
-    rc = attn_fwd_raw(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
-                      lse.data_ptr() if lse is not None else 0, B, H, S, D, causal, scale, dtype, st)
+    rc = (attn_fwd_o16_raw if _o16 else attn_fwd_raw)(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                                      lse.data_ptr() if lse is not None else 0, B, H, S, D, causal, scale,
+                                                      dtype, st)
     if rc != 0:
         raise AttnError(rc, attn_status_str(rc))
     return o, lse

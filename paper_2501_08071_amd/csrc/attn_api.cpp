@@ -49,8 +49,9 @@ extern "C" int attn_tile_keys(int D, int dtype, int causal) {
     return attn_supported(1, D, dtype, causal) ? ATTN_BC : 0;
 }
 
-extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int B, int H, int S, int D,
-                        int causal, float scale, int dtype, void* stream) {
+namespace {
+int fwd(const void* q, const void* k, const void* v, void* o, int o16, float* lse, int B, int H, int S, int D, int causal,
+        float scale, int dtype, void* stream) {
     if (!q || !k || !v || !o) return ATTN_ERR_NULL;
     if (B <= 0 || H <= 0 || S <= 0 || D <= 0) return ATTN_ERR_SHAPE;
     const long long bh = (long long)B * H;
@@ -70,6 +71,7 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, f
     // to fp32, so scale == 0 keeps its meaning)
     a.c = std::fmax(std::fabs(scale) * 1.4426950408889634f, 1e-30f);
     a.qsign = std::signbit(scale) && scale != 0.f ? 0x80008000u : 0u;
+    a.o16 = o16;
     a.stream = stream;
     const hipError_t err = attn_launch(a);
     if (err != hipSuccess) {
@@ -77,4 +79,15 @@ extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, f
         return ATTN_ERR_LAUNCH;
     }
     return ATTN_OK;
+}
+}  // namespace
+
+extern "C" int attn_fwd(const void* q, const void* k, const void* v, float* o, float* lse, int B, int H, int S, int D,
+                        int causal, float scale, int dtype, void* stream) {
+    return fwd(q, k, v, o, 0, lse, B, H, S, D, causal, scale, dtype, stream);
+}
+
+extern "C" int attn_fwd_o16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int S, int D,
+                            int causal, float scale, int dtype, void* stream) {
+    return fwd(q, k, v, o, 1, lse, B, H, S, D, causal, scale, dtype, stream);
 }

@@ -134,8 +134,8 @@ extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 template <int DT, int D, bool CAUSAL, int NW>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ATTN_WPE, ATTN_WPE)))
 void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-                     float* __restrict__ o, float* __restrict__ lse, int S, int BH, int nqt, float c_arg,
-                     uint32_t qsign) {
+                     void* __restrict__ o, float* __restrict__ lse, int S, int BH, int nqt, float c_arg,
+                     uint32_t qsign, int o16) {
     using E = Elem<DT>;
     constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
     constexpr int BC = ATTN_BC;        // keys per block
@@ -645,15 +645,27 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
     if (qrow < S) {
-        float* orow = o + head + (size_t)qrow * D;
+        if (o16 == 0) {
+            float* orow = (float*)o + head + (size_t)qrow * D;
 #pragma unroll
-        for (int i = 0; i < DB; ++i)
+            for (int i = 0; i < DB; ++i)
 #pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {
-                f32x4 x = {acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv, acc_o[i][4 * gg + 2] * inv,
-                           acc_o[i][4 * gg + 3] * inv};
-                *(f32x4*)(orow + 32 * i + 8 * gg + 4 * h) = x;
-            }
+                for (int gg = 0; gg < 4; ++gg) {
+                    f32x4 x = {acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv, acc_o[i][4 * gg + 2] * inv,
+                               acc_o[i][4 * gg + 3] * inv};
+                    *(f32x4*)(orow + 32 * i + 8 * gg + 4 * h) = x;
+                }
+        } else {   // O in the input type, rounded to nearest even: 4 elements = 8 bytes per store
+            uint16_t* orow = (uint16_t*)o + head + (size_t)qrow * D;
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) {
+                    u32x2 x = {E::pack2(acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv),
+                               E::pack2(acc_o[i][4 * gg + 2] * inv, acc_o[i][4 * gg + 3] * inv)};
+                    *(u32x2*)(orow + 32 * i + 8 * gg + 4 * h) = x;
+                }
+        }
         if (lse != nullptr && h == 0)
             lse[(size_t)bh * S + qrow] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     }
@@ -668,12 +680,12 @@ hipError_t launch(const AttnLaunch& a) {
     const uint16_t* q = (const uint16_t*)a.q;
     const uint16_t* k = (const uint16_t*)a.k;
     const uint16_t* v = (const uint16_t*)a.v;
-    float* o = a.o;
+    void* o = a.o;
     float* lse = a.lse;
-    int S = a.S, BH = a.BH, nq = nqt;
+    int S = a.S, BH = a.BH, nq = nqt, o16 = a.o16;
     float c = a.c;
     uint32_t qsign = a.qsign;
-    void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign};
+    void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign, &o16};
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
     constexpr unsigned lds_bytes = 2u * ATTN_NBUF * ATTN_BC * 2u * D;   // NBUF K and NBUF V block buffers

@@ -30,13 +30,14 @@ struct AttnLaunch {
     const void* q;
     const void* k;
     const void* v;
-    float* o;
+    void* o;          // fp32, or the input type when o16 is set
     float* lse;       // may be null
     int BH, S, D;
     int causal;
     int dtype;        // 0 binary16, 1 bfloat16
     float c;          // |scale| * log2(e)
     uint32_t qsign;   // 0x80008000 when scale < 0 (sign folded into q), else 0
+    int o16;          // write O rounded to the input type instead of fp32
     void* stream;
 };
 

@@ -19,12 +19,12 @@ def P():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "attn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(attn_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(attn_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(P):
     names = declared_symbols()
-    assert {"attn_fwd", "attn_supported", "attn_status_str"} <= set(names)
+    assert {"attn_fwd", "attn_fwd_o16", "attn_supported", "attn_status_str"} <= set(names)
     for n in names:
         assert hasattr(P.lib, n), f"{n} is declared in attn.h but not exported"
 
@@ -52,9 +52,10 @@ def test_supported_matrix(P):
     assert P.attn_kernel_name(128, 96, 0, False) is None
 
 
-def test_bad_arguments_rejected_without_a_gpu(P):
+@pytest.mark.parametrize("entry", ["attn_fwd_raw", "attn_fwd_o16_raw"])
+def test_bad_arguments_rejected_without_a_gpu(P, entry):
     ok = 4096  # any non-null 16-byte aligned address: validation fails before it is touched
-    f = P.attn_fwd_raw
+    f = getattr(P, entry)
     assert f(0, ok, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1
     assert f(ok, 0, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1
     assert f(ok, ok, 0, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -1

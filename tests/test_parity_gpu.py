@@ -88,6 +88,24 @@ def test_moving_reference_maximum(dtype, D, causal, kind):
     check_full(q, k, v, dtype, causal, 1.0, f"{kind} logits D={D}")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype,D,S", [(F16, 64, 333), (BF16, 128, 300), (F16, 128, 257), (BF16, 64, 129)])
+def test_output_in_input_dtype(dtype, D, S, causal):
+    """attn_fwd_o16: O rounded to the input type is the fp32 O of attn_fwd, rounded (bit for bit), and
+    meets the same bar against the oracle; lse is the same."""
+    q, k, v = I.gen_tensors(2, 2, S, D, dtype, workload_id=400 + D)
+    dq, dk, dv = (to_device(t, dtype) for t in (q, k, v))
+    scale = 1.0 / math.sqrt(D)
+    o32, lse32 = P.attn_fwd(dq, dk, dv, causal, scale)
+    o16, lse16 = P.attn_fwd_o16(dq, dk, dv, causal, scale)
+    torch.cuda.synchronize()
+    assert o16.dtype == dq.dtype
+    assert torch.equal(o16, o32.to(dq.dtype))          # torch rounds to nearest even, as the kernel does
+    assert torch.equal(lse16, lse32)
+    o_ref, lse_ref = oracle.attn_oracle(q, k, v, causal, scale, dtype)
+    assert_parity(o16.float().cpu().numpy(), lse16.cpu().numpy(), o_ref, lse_ref, f"o16 D={D} S={S}")
+
+
 def test_closed_forms_on_gpu():
     S, D = 300, 64
     q, k, v = I.gen_tensors(1, 2, S, D, F16, workload_id=203)
