@@ -11,14 +11,21 @@
 //
 // K/V movement
 //   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), ATTN_NBUF buffers per tensor,
-//   loads issued about ATTN_NBUF blocks ahead of their use, one barrier per two blocks.  Such a load writes 1 KiB
-//   of consecutive LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an
-//   XOR swizzle of the 16-byte chunk index within each row, applied on the global-address side.
+//   loads issued about ATTN_NBUF blocks ahead of their use.  Such a load writes 1 KiB of consecutive
+//   LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an XOR swizzle of the
+//   16-byte chunk index within each row, applied on the global-address side.
 //
-// Software pipeline (per wavefront, one "slot" per key block k)
-//   matrix pipe:  S(k+1) = K(k+1).Q^T   and   O += V(k-1)^T.P(k-1)^T
-//   vector pipe:  P(k) = exp2(c S(k) - m)  (+ row sum, rounding to the input type)
-//   so neither product waits for the exponentials of its own block.
+// Schedule
+//   The two wavefronts of a SIMD share one issue port for vector and matrix instructions, and the
+//   vector work of a key block (16 fma, 16 exp, 16 add, 8 convert per lane) is of the order of its
+//   matrix work (16 matrix instructions at D = 128, 8 at D = 64).  Two loop structures:
+//   D = 128  two groups of wavefronts run matrix phases M(k): S(k) = K(k).Q^T, O += V(k-1)^T.P(k-1)^T
+//            and vector phases V(k): P(k) = exp2(c S(k) - m) half a block apart, a barrier between
+//            phases: on every SIMD one wavefront feeds the matrix pipe while the other has the vector port;
+//   D = 64   every wavefront interleaves the matrix instructions of S(k+1) and O += V(k-1)^T.P(k-1)^T
+//            with the vector work of P(k); one barrier per two blocks.
+//   The softmax reference m of a row is the maximum of its first block; it is only taken again when a
+//   block's weight sum overflows a threshold (no row maxima on the hot path).
 //
 // Register layout (64-wide wavefront, lane l, half h = l/32, l32 = l%32)
 //   Everything is computed transposed so that one lane only ever holds values of ONE query row:

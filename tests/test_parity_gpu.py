@@ -162,6 +162,40 @@ def test_non_default_stream_and_guard_bytes():
     assert_parity(o.cpu().numpy(), lse.cpu().numpy(), o_ref, l_ref, "side stream")
 
 
+def test_graph_capture_and_replay():
+    """The call is one asynchronous kernel launch with no allocation and no synchronisation, so it can be
+    captured into a HIP graph; every replay, with new inputs written in place and eager work in between,
+    gives the eager result bit for bit."""
+    B, H, S = 1, 2, 300
+    cases = []
+    for D, dtype, causal in ((128, BF16, True), (64, F16, False)):
+        q, k, v = I.gen_tensors(B, H, S, D, dtype, workload_id=500 + D)
+        dq, dk, dv = (to_device(t, dtype) for t in (q, k, v))
+        o = torch.empty((B, H, S, D), dtype=torch.float32, device="cuda")
+        lse = torch.empty((B, H, S), dtype=torch.float32, device="cuda")
+        P.attn_fwd(dq, dk, dv, causal, 0.1, o=o, lse=lse)          # first call outside the capture
+        cases.append((dq, dk, dv, causal, o, lse))
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for dq, dk, dv, causal, o, lse in cases:
+            P.attn_fwd(dq, dk, dv, causal, 0.1, o=o, lse=lse)
+    for rep in range(3):
+        for dq, dk, dv, causal, o, lse in cases:
+            dq.copy_(torch.roll(dq, rep + 1, dims=2)); dv.mul_(-1.0)      # new inputs, in place
+            o.fill_(float("nan")); lse.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for dq, dk, dv, causal, o, lse in cases:
+            o_e, lse_e = P.attn_fwd(dq, dk, dv, causal, 0.1)
+            torch.cuda.synchronize()
+            assert torch.equal(o, o_e) and torch.equal(lse, lse_e), f"replay {rep}"
+    dq, dk, dv, causal, o, lse = cases[0]
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    o_ref, l_ref = oracle.attn_oracle(bits(dq), bits(dk), bits(dv), causal, 0.1, BF16)
+    assert_parity(o.cpu().numpy(), lse.cpu().numpy(), o_ref, l_ref, "graph replay")
+
+
 # ---- the five workloads at full size, in the launch configuration the bench times -------
 
 @pytest.mark.parametrize("wid", [2, 3, 4, 5])
