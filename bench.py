@@ -84,7 +84,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--workload", type=int, default=3, help="1..5; 3 is the headline (S=4096, D=128, causal, bf16)")
+    ap.add_argument("--workload", type=int, default=3,
+                    help="1..5; 3 is the headline (S=4096, D=128, causal, bf16); 6, 7: the paper's own attention shape")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cold", action="store_true", help="also time with caches flushed between launches")
     ap.add_argument("--seed", type=int, default=None)

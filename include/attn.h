@@ -48,7 +48,7 @@ typedef enum {
  *   lse      DEVICE pointer, [B,H,S] fp32, natural-log logsumexp of the scaled,
  *            masked logits; may be NULL (then it is not written).
  *   B,H,S,D  batch, heads, sequence length (queries == keys), head dimension.
- *            Any S >= 1; D must be 64 or 128.
+ *            Any S >= 1; D must be 32, 64 or 128.
  *   causal   0: every key visible; non-zero: key j visible to query i iff j <= i.
  *   scale    multiplies q.k before the softmax; any finite value.
  *   dtype    attn_dtype_t of q, k, v.

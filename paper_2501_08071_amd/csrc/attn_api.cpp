@@ -9,7 +9,7 @@
 #include "attn_launch.h"
 
 namespace {
-bool d_supported(int D) { return D == 64 || D == 128; }
+bool d_supported(int D) { return D == 32 || D == 64 || D == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 }  // namespace
 
@@ -25,7 +25,7 @@ extern "C" const char* attn_status_str(int status) {
         case ATTN_ERR_SHAPE: return "B, H, S and D must be positive (and a tensor at most 2^40 elements)";
         case ATTN_ERR_DTYPE: return "dtype must be ATTN_F16 (0) or ATTN_BF16 (1)";
         case ATTN_ERR_SCALE: return "scale must be finite";
-        case ATTN_ERR_UNSUPPORTED: return "no kernel instance for this head dimension (D must be 64 or 128)";
+        case ATTN_ERR_UNSUPPORTED: return "no kernel instance for this head dimension (D must be 32, 64 or 128)";
         case ATTN_ERR_ALIGN: return "every pointer must be 16-byte aligned";
         case ATTN_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
         default: return "unknown status";
@@ -34,8 +34,8 @@ extern "C" const char* attn_status_str(int status) {
 
 extern "C" const char* attn_kernel_name(int S, int D, int dtype, int causal) {
     if (!attn_supported(S, D, dtype, causal)) return nullptr;
-    static char names[2][2][2][64];
-    char* n = names[dtype][D == 128][causal != 0];
+    static char names[2][3][2][64];
+    char* n = names[dtype][D == 32 ? 0 : D == 64 ? 1 : 2][causal != 0];
     if (n[0] == 0)
         std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d>", dtype, D, causal ? "true" : "false", ATTN_NW);
     return n;

@@ -130,10 +130,13 @@ __device__ __forceinline__ float other_half(float x) {
 //   reads of V): swap the two low bit pairs of the row index.
 // D=64 (8 chunks/row, two rows span the banks): the same two conditions with the row parity
 //   already selecting the bank half: bit-reverse bits 1..3 of the row index.
+// D=32 (4 chunks/row, four rows span the banks): row % 4 selects the bank quarter, so the transpose
+//   reads need nothing; for the b128 reads rows r, r+4, r+8, r+12 must differ: bits 2..3 of the row.
 template <int D>
 __device__ __forceinline__ constexpr int swz(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))
-                    : ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1));
+           : D == 64 ? ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1))
+                     : ((row >> 2) & 3);
 }
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
@@ -248,8 +251,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // the last V buffer is read by slot 0 (with all-zero weights) before anything was loaded into it:
     // make its contents finite
     {
-        constexpr int PER = BLKB / (NW * 64);
+        constexpr int PER = BLKB / (NW * 64);   // bytes per thread
+        static_assert(PER % 16 == 0 || PER == 8 || PER == 4, "zero fill");
         uint8_t* vb3 = smem + (2 * NBUF - 1) * BLKB + tid * PER;
+        if constexpr (PER == 4) *(uint32_t*)vb3 = 0u;
+        if constexpr (PER == 8) *(u32x2*)vb3 = u32x2{0u, 0u};
 #pragma unroll
         for (int i = 0; i < PER / 16; ++i) *(u32x4*)(vb3 + 16 * i) = u32x4{0u, 0u, 0u, 0u};
     }
@@ -714,6 +720,10 @@ hipError_t launch(const AttnLaunch& a) {
 hipError_t attn_launch(const AttnLaunch& a) {
 #define ATTN_CASE(DT, DD, CZ)                                       \
     if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW>(a);
+    ATTN_CASE(0, 32, false)
+    ATTN_CASE(0, 32, true)
+    ATTN_CASE(1, 32, false)
+    ATTN_CASE(1, 32, true)
     ATTN_CASE(0, 64, false)
     ATTN_CASE(0, 64, true)
     ATTN_CASE(0, 128, false)

@@ -69,10 +69,16 @@ WORKLOADS = (
     Workload(4, "B1_H32_S16384_D128_bf16_causal", 1, 32, 16384, 128, BF16, True, "normal", 1.0, "normal"),
     Workload(5, "B16_H16_S2048_D64_f16_peaky", 16, 16, 2048, 64, F16, False, "normal", 4.0, "uniform_pm1"),
 )
+# Not one of the five: the shape the paper runs its flash-attention kernel on (Table 2: B, n_head, seq_len,
+# d_head = 1, 4, 4096, 32, fp16); the paper does not say whether it is causal, both are kept.
+EXTRA_WORKLOADS = (
+    Workload(6, "B1_H4_S4096_D32_f16_paper", 1, 4, 4096, 32, F16, False, "normal", 1.0, "normal"),
+    Workload(7, "B1_H4_S4096_D32_f16_paper_causal", 1, 4, 4096, 32, F16, True, "normal", 1.0, "normal"),
+)
 
 
 def workload(wid: int) -> Workload:
-    return WORKLOADS[wid - 1]
+    return (WORKLOADS + EXTRA_WORKLOADS)[wid - 1]
 
 
 # ---- SplitMix64 -------------------------------------------------------------------------

@@ -40,13 +40,13 @@ def test_status_strings(P):
 
 
 def test_supported_matrix(P):
-    for D in (64, 128):
+    for D in (32, 64, 128):
         for dt in (0, 1):
             for causal in (False, True):
                 assert P.attn_supported(1, D, dt, causal) and P.attn_supported(16384, D, dt, causal)
                 assert P.attn_kernel_name(128, D, dt, causal)
                 assert P.attn_tile_rows(D, dt, causal) % 32 == 0 and P.attn_tile_keys(D, dt, causal) > 0
-    assert not P.attn_supported(128, 32, 0, False)
+    assert not P.attn_supported(128, 16, 0, False) and not P.attn_supported(128, 256, 0, False)
     assert not P.attn_supported(128, 64, 2, False)
     assert not P.attn_supported(0, 64, 0, False)
     assert P.attn_kernel_name(128, 96, 0, False) is None

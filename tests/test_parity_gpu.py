@@ -21,6 +21,7 @@ SMALL = [
     (2, 2, 1, 64), (1, 2, 2, 128), (1, 3, 31, 64), (1, 2, 33, 128), (2, 1, 64, 64), (1, 2, 65, 128),
     (1, 2, 127, 64), (1, 1, 128, 128), (1, 2, 129, 64), (2, 2, 200, 128), (1, 3, 257, 64), (1, 2, 300, 128),
     (2, 2, 517, 64), (1, 2, 640, 128),
+    (2, 2, 1, 32), (1, 2, 33, 32), (1, 3, 127, 32), (2, 1, 256, 32), (1, 2, 300, 32), (1, 2, 777, 32),
 ]
 
 
@@ -80,7 +81,7 @@ def _trend_inputs(S, D, dtype, kind, seed):
 
 @pytest.mark.parametrize("kind", ["rising", "falling", "spike"])
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("dtype,D", [(F16, 64), (BF16, 128), (F16, 128), (BF16, 64)])
+@pytest.mark.parametrize("dtype,D", [(F16, 64), (BF16, 128), (F16, 128), (BF16, 64), (F16, 32), (BF16, 32)])
 def test_moving_reference_maximum(dtype, D, causal, kind):
     """The kernel takes row maxima only when a block's weight sum overflows a threshold: drive that path
     many times (rising), never (falling), and once with a jump of many orders of magnitude (spike)."""
@@ -160,6 +161,14 @@ def test_non_default_stream_and_guard_bytes():
     assert (lbuf[:pad] == 7).all() and (lbuf[-pad:] == 7).all()
     o_ref, l_ref = oracle.attn_oracle(q, k, v, True, 0.125, BF16)
     assert_parity(o.cpu().numpy(), lse.cpu().numpy(), o_ref, l_ref, "side stream")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_paper_attention_shape(causal):
+    """The shape the paper evaluates its flash-attention kernel on (Table 2: B=1, n_head=4, seq_len=4096,
+    d_head=32, fp16), every output element compared."""
+    q, k, v = I.gen_tensors(1, 4, 4096, 32, F16, workload_id=600)
+    check_full(q, k, v, F16, causal, 1.0 / math.sqrt(32), f"paper shape causal={causal}")
 
 
 def test_graph_capture_and_replay():
