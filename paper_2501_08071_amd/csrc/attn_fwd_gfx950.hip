@@ -447,11 +447,22 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             v_phase(kb, phase);
             __builtin_amdgcn_sched_barrier(0);
         };
-        // Under the causal mask a wavefront is done after M(kd+1), which adds the second product of its
-        // diagonal block kd: every later block of the workgroup is masked entirely for it (and V(kd+1)
-        // has left all-zero weights for the closing product after the loop).  From then on it only
-        // issues its share of the block loads and keeps the barriers.
-        const int last_w = CAUSAL && kd + 1 < last_max ? kd + 1 : last_max;
+        // The second product of a wavefront's last block, all operand reads first.
+        auto closing_product = [&](int VB) {
+            u32x4 a[2][DB];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int i = 0; i < DB; ++i) a[tt][i] = fetch_v(VB, tt, i);
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int i = 0; i < DB; ++i) acc_o[i] = E::mfma(a[tt][i], pf[tt], acc_o[i]);
+        };
+        // Under the causal mask a wavefront is done with its diagonal block kd: every later block of the
+        // workgroup is masked entirely for it.  In the time of block kd+1 it adds the second product of
+        // block kd; from then on it only issues its share of the block loads and keeps the barriers.
+        const int last_w = CAUSAL && kd < last_max ? kd : last_max;
         for (int k0 = 0; k0 <= last_w; k0 += NBUF) {
             [&]<int... PH>(std::integer_sequence<int, PH...>) {
                 ((k0 + PH <= last_w ? block(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
@@ -460,6 +471,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         for (int kb = last_w + 1; kb <= last_max; ++kb) {
             wait_block_loads<(KAHEAD + VAHEAD - 5) * IPW>();
             asm volatile("s_barrier" ::: "memory");
+            if (kb == last_w + 1) closing_product(last_w & (NBUF - 1));
 #pragma unroll
             for (int P = 0; P < 2 * IPW; ++P) {
                 const int W = P / IPW, AHEAD = W ? VAHEAD : KAHEAD;
@@ -468,9 +480,10 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             asm volatile("s_barrier" ::: "memory");
         }
         if (!grp1) asm volatile("s_barrier" ::: "memory");   // the first group's last one
-        // The second product of the last block is still open.  Every wavefront made sure of its share of
-        // V(last) two blocks ago at the latest, and has passed a barrier since.
-        pv_plain(pf, last_max & (NBUF - 1));
+        // A wavefront that went through to the workgroup's last block still has that block's second
+        // product open.  Every wavefront made sure of its share of V(last) two blocks ago at the latest,
+        // and has passed a barrier since.
+        if (last_w == last_max) closing_product(last_max & (NBUF - 1));
         m_run = m_ref;
     } else {
         // first ATTN_FETCH operands of the next slot, read before its barrier (so that the matrix pipe does not
