@@ -171,6 +171,16 @@ def test_paper_attention_shape(causal):
     check_full(q, k, v, F16, causal, 1.0 / math.sqrt(32), f"paper shape causal={causal}")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("S", [300, 512, 1000])
+def test_more_tiles_than_compute_units(S, causal):
+    """More workgroups than the chip runs at once (320 to 640 tiles of 256 query rows), whole (S = 512) and
+    ragged (S = 300, 1000) key streams, every output element compared."""
+    B, H = 4, 40
+    q, k, v = I.gen_tensors(B, H, S, 128, BF16, workload_id=700 + S)
+    check_full(q, k, v, BF16, causal, 1.0 / math.sqrt(128), f"many tiles S={S} causal={causal}")
+
+
 def test_graph_capture_and_replay():
     """The call is one asynchronous kernel launch with no allocation and no synchronisation, so it can be
     captured into a HIP graph; every replay, with new inputs written in place and eager work in between,
