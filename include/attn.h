@@ -69,7 +69,8 @@ int attn_fwd(const void *q, const void *k, const void *v, float *o, float *lse,
 /*
  * The same operation with O written in the type of q, k and v (Table 2 gives the kernel's inputs as
  * fp16 tensors; a layer that feeds the next one in half precision wants O that way), rounded to
- * nearest even from the fp32 result.  `o` is [B,H,S,D] contiguous in `dtype`; lse stays fp32.  Every
+ * nearest even from the fp32 result (so its error is that of attn_fwd plus one rounding of O: at most
+ * 2^-9 |O| for bfloat16, 2^-12 |O| for binary16).  `o` is [B,H,S,D] contiguous in `dtype`; lse stays fp32.  Every
  * other argument, the ownership and error rules are those of attn_fwd; both share one kernel.
  */
 int attn_fwd_o16(const void *q, const void *k, const void *v, void *o, float *lse,

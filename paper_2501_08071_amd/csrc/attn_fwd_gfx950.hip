@@ -180,9 +180,28 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     const int l32 = lane & 31;
     const int h = lane >> 5;
 
-    // heaviest query tiles first (under the causal mask tile t reads t+1 key tiles)
-    const int bh = blockIdx.x % BH;
-    const int qt = CAUSAL ? nqt - 1 - blockIdx.x / BH : blockIdx.x / BH;
+    // Workgroup -> tile.  Workgroups are handed to the eight XCDs in turn (workgroup b runs on XCD b % 8,
+    // each with an L2 of its own), in the order of their number.  The (b,h) pairs are therefore dealt out
+    // by XCD (bh % 8 = b % 8) and, on an XCD, taken ATTN_HEAD_GROUP at a time: all query tiles of those
+    // few heads -- heaviest first: under the causal mask query tile t reads t+1 key tiles -- before the
+    // next heads.  Tiles that stream the same K and V then run at the same time on the same L2.  With a
+    // number of heads that does not divide that way: heaviest tiles first over all heads.
+    int bh, qt;
+    {
+        constexpr int GS = ATTN_HEAD_GROUP;
+        const int b = blockIdx.x;
+        if (GS > 0 && BH % (8 * GS) == 0 && (gridDim.x & 7) == 0) {
+            const int x = b & 7, j = b >> 3;          // XCD, and position in its queue
+            const int per = GS * nqt;                 // tiles per group of heads
+            const int p = j / per, r = j - p * per;
+            qt = r / GS;
+            bh = x + 8 * (p * GS + (r - qt * GS));
+        } else {
+            bh = b % BH;
+            qt = b / BH;
+        }
+        if (CAUSAL) qt = nqt - 1 - qt;
+    }
     const int q0 = qt * BR;
     const int qw0 = q0 + 32 * wave;          // first query row of this wavefront
     const int qrow = qw0 + l32;              // this lane's query row (may lie beyond S on the last tile)

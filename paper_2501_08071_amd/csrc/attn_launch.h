@@ -19,6 +19,9 @@
 #ifndef ATTN_PINGPONG
 #define ATTN_PINGPONG 1  // D = 128: alternate matrix and vector phases between two groups of wavefronts
 #endif
+#ifndef ATTN_HEAD_GROUP
+#define ATTN_HEAD_GROUP 4  // (b,h) pairs whose query tiles an XCD works on at the same time (0: no grouping)
+#endif
 #ifndef ATTN_FETCH
 #define ATTN_FETCH 4  // units between the LDS read of an operand and the matrix instruction that uses it
 #endif
