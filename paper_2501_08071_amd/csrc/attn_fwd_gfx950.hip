@@ -689,28 +689,42 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l) ----
     const float l_tot = l_run + other_half(l_run);
     const float inv = 1.0f / l_tot;
-    if (qrow < S) {
-        if (o16 == 0) {
-            float* orow = (float*)o + head + (size_t)qrow * D;
+    if (o16 == 0) {
+        // Single precision O.  A lane holds 4 consecutive elements of its own row: stored from there, one
+        // instruction would touch 32 rows with 32 bytes each.  The tile goes through LDS instead, 32 columns
+        // (4 KB, a region of the wavefront's own behind the block buffers) at a time, and comes back with
+        // 8 lanes side by side on a row: every store instruction then writes 8 whole 128-byte lines.
+        // 16-byte chunk c of row r sits at chunk position c ^ ((r / 2) % 8): the writes (16 rows, one
+        // chunk column) and the reads (2 rows, all chunks) both spread over all banks.
+        uint8_t* xp = smem + 2 * NBUF * BLKB + wave * 4096;
+        float* obase = (float*)o + head + (size_t)qw0 * D;
 #pragma unroll
-            for (int i = 0; i < DB; ++i)
+        for (int i = 0; i < DB; ++i) {
 #pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    f32x4 x = {acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv, acc_o[i][4 * gg + 2] * inv,
-                               acc_o[i][4 * gg + 3] * inv};
-                    *(f32x4*)(orow + 32 * i + 8 * gg + 4 * h) = x;
-                }
-        } else {   // O in the input type, rounded to nearest even: 4 elements = 8 bytes per store
-            uint16_t* orow = (uint16_t*)o + head + (size_t)qrow * D;
+            for (int gg = 0; gg < 4; ++gg) {
+                f32x4 x = {acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv, acc_o[i][4 * gg + 2] * inv,
+                           acc_o[i][4 * gg + 3] * inv};
+                *(f32x4*)(xp + l32 * 128 + (((2 * gg + h) ^ ((l32 >> 1) & 7)) << 4)) = x;
+            }
 #pragma unroll
-            for (int i = 0; i < DB; ++i)
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg) {
-                    u32x2 x = {E::pack2(acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv),
-                               E::pack2(acc_o[i][4 * gg + 2] * inv, acc_o[i][4 * gg + 3] * inv)};
-                    *(u32x2*)(orow + 32 * i + 8 * gg + 4 * h) = x;
-                }
+            for (int pass = 0; pass < 4; ++pass) {
+                const int row = 8 * pass + (lane >> 3), ch = lane & 7;
+                const f32x4 y = *(const f32x4*)(xp + row * 128 + ((ch ^ ((row >> 1) & 7)) << 4));
+                if (qw0 + row < S) *(f32x4*)(obase + (size_t)row * D + 32 * i + 4 * ch) = y;
+            }
         }
+    } else if (qrow < S) {   // O in the input type, rounded to nearest even: 4 elements = 8 bytes per store
+        uint16_t* orow = (uint16_t*)o + head + (size_t)qrow * D;
+#pragma unroll
+        for (int i = 0; i < DB; ++i)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                u32x2 x = {E::pack2(acc_o[i][4 * gg] * inv, acc_o[i][4 * gg + 1] * inv),
+                           E::pack2(acc_o[i][4 * gg + 2] * inv, acc_o[i][4 * gg + 3] * inv)};
+                *(u32x2*)(orow + 32 * i + 8 * gg + 4 * h) = x;
+            }
+    }
+    if (qrow < S) {
         if (lse != nullptr && h == 0)
             lse[(size_t)bh * S + qrow] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
     }
@@ -733,7 +747,8 @@ hipError_t launch(const AttnLaunch& a) {
     void* args[] = {&q, &k, &v, &o, &lse, &S, &BH, &nq, &c, &qsign, &o16};
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
-    constexpr unsigned lds_bytes = 2u * ATTN_NBUF * ATTN_BC * 2u * D;   // NBUF K and NBUF V block buffers
+    // NBUF K and NBUF V block buffers, and 4 KB per wavefront for the way out of the output tile
+    constexpr unsigned lds_bytes = 2u * ATTN_NBUF * ATTN_BC * 2u * D + NW * 4096u;
     const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>);
     if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
         static bool raised = false;
