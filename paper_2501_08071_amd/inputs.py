@@ -186,3 +186,17 @@ def gen_inputs(w: Workload, seed: int = BASE_SEED):
     """The three input tensors of a named workload."""
     return gen_tensors(w.B, w.H, w.S, w.D, w.dtype, workload_id=w.id, seed=seed,
                        qk_mul=w.qk_mul, v_dist=w.v_dist)
+
+
+# ---- row operations (the paper's memory-bound kernels, Table 2) ---------------------------
+
+ROWOP_SHAPES = {
+    "softmax_512x4096_f16": ("softmax", 512, 4096, F16),            # n_rows, n_cols (Table 2)
+    "rmsnorm_1x32x4096x64_f16": ("rmsnorm", 1 * 32 * 4096, 64, F16),   # B * n_head * seq_len rows of d_head (Table 2)
+}
+
+
+def gen_rows(n_rows: int, n_cols: int, dtype: int, *, tensor_id: int = 0, seed: int = BASE_SEED,
+             dist: str = "normal", mul: float = 1.0) -> np.ndarray:
+    """A seeded [n_rows, n_cols] matrix of 16-bit patterns (tensor_id separates x from the weight)."""
+    return _fill(tensor_seed(seed, 100, tensor_id), n_rows * n_cols, dist, mul, dtype).reshape(n_rows, n_cols)
