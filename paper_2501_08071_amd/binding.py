@@ -46,6 +46,15 @@ def _load() -> ctypes.CDLL:
     for f in (lib.attn_tile_rows, lib.attn_tile_keys):
         f.argtypes = [ctypes.c_int] * 3
         f.restype = ctypes.c_int
+    # include/rowops.h
+    lib.softmax_rows_fwd.argtypes = [vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
+    lib.softmax_rows_fwd.restype = ctypes.c_int
+    lib.rmsnorm_fwd.argtypes = [vp, vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_float, ctypes.c_int, vp]
+    lib.rmsnorm_fwd.restype = ctypes.c_int
+    lib.rowops_path.argtypes = [ctypes.c_int] * 3
+    lib.rowops_path.restype = ctypes.c_int
+    lib.rowops_status_str.argtypes = [ctypes.c_int]
+    lib.rowops_status_str.restype = ctypes.c_char_p
     return lib
 
 
@@ -131,3 +140,69 @@ def attn_fwd(q, k, v, causal: bool, scale: float, o=None, lse=None, stream=None,
     if rc != 0:
         raise AttnError(rc, attn_status_str(rc))
     return o, lse
+
+
+# ---- include/rowops.h ------------------------------------------------------------------------
+
+class RowopsError(RuntimeError):
+    def __init__(self, what: str, status: int, msg: str):
+        super().__init__(f"{what} failed with status {status}: {msg}")
+        self.status = status
+
+
+def rowops_status_str(status: int) -> str:
+    return lib.rowops_status_str(int(status)).decode()
+
+
+def rowops_path(op: int, row_len: int, dtype: int) -> int:
+    return int(lib.rowops_path(int(op), int(row_len), int(dtype)))
+
+
+def softmax_rows_fwd_raw(x_ptr, y_ptr, n_rows, n_cols, dtype, stream) -> int:
+    """The C entry point as is: device addresses as ints (0 = NULL), returns the status."""
+    return int(lib.softmax_rows_fwd(x_ptr or None, y_ptr or None, int(n_rows), int(n_cols), int(dtype), stream or None))
+
+
+def rmsnorm_fwd_raw(x_ptr, w_ptr, y_ptr, n_rows, d, eps, dtype, stream) -> int:
+    """The C entry point as is: device addresses as ints (0 = NULL), returns the status."""
+    return int(lib.rmsnorm_fwd(x_ptr or None, w_ptr or None, y_ptr or None, int(n_rows), int(d), float(eps), int(dtype),
+                               stream or None))
+
+
+def _row_args(x, y):
+    if x.dtype == torch.float16:
+        dtype = F16
+    elif x.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("x must be float16 or bfloat16")
+    if x.dim() < 1 or not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous device tensor with the rows along the last dimension")
+    if y is None:
+        y = torch.empty_like(x)
+    elif y.dtype != x.dtype or y.shape != x.shape or not y.is_cuda or not y.is_contiguous():
+        raise ValueError("y must be a contiguous device tensor of the shape and dtype of x")
+    n = x.shape[-1]
+    return dtype, y, (x.numel() // n if n else 0), n
+
+
+def softmax_rows_fwd(x, y=None, stream=None):
+    """softmax_rows_fwd on a torch device tensor: softmax over the last dimension, result in x's dtype."""
+    dtype, y, n_rows, n = _row_args(x, y)
+    st = (stream or torch.cuda.current_stream(x.device)).cuda_stream
+    rc = softmax_rows_fwd_raw(x.data_ptr(), y.data_ptr(), n_rows, n, dtype, st)
+    if rc != 0:
+        raise RowopsError("softmax_rows_fwd", rc, rowops_status_str(rc))
+    return y
+
+
+def rmsnorm_fwd(x, w, eps: float, y=None, stream=None):
+    """rmsnorm_fwd on torch device tensors: x [..., d], w [d] of one dtype; result in x's dtype."""
+    dtype, y, n_rows, n = _row_args(x, y)
+    if w.dtype != x.dtype or tuple(w.shape) != (n,) or not w.is_cuda or not w.is_contiguous():
+        raise ValueError("w must be a contiguous device tensor [d] of x's dtype")
+    st = (stream or torch.cuda.current_stream(x.device)).cuda_stream
+    rc = rmsnorm_fwd_raw(x.data_ptr(), w.data_ptr(), y.data_ptr(), n_rows, n, eps, dtype, st)
+    if rc != 0:
+        raise RowopsError("rmsnorm_fwd", rc, rowops_status_str(rc))
+    return y

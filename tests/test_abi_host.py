@@ -22,11 +22,54 @@ def declared_symbols():
     return sorted(set(re.findall(r"\b(attn_[a-z0-9_]+)\s*\(", text)))
 
 
+def declared_rowops_symbols():
+    text = open(os.path.join(ROOT, "include", "rowops.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:rowops_|softmax_rows_|rmsnorm_)[a-z0-9_]+)\s*\(", text)))
+
+
 def test_every_declared_symbol_is_exported(P):
     names = declared_symbols()
     assert {"attn_fwd", "attn_fwd_o16", "attn_supported", "attn_status_str"} <= set(names)
     for n in names:
         assert hasattr(P.lib, n), f"{n} is declared in attn.h but not exported"
+    names = declared_rowops_symbols()
+    assert names == ["rmsnorm_fwd", "rowops_path", "rowops_status_str", "softmax_rows_fwd"]
+    for n in names:
+        assert hasattr(P.lib, n), f"{n} is declared in rowops.h but not exported"
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["attn.h", "rowops.h"]
+
+
+def test_rowops_status_strings_and_paths(P):
+    seen = {P.rowops_status_str(st) for st in (0, -1, -2, -3, -4, -6, -7)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert P.rowops_status_str(-5) == "unknown status" and P.rowops_status_str(3) == "unknown status"
+    for op in (0, 1):
+        for dt in (0, 1):
+            assert P.rowops_path(op, 8, dt) == 1 and P.rowops_path(op, 64, dt) == 1 and P.rowops_path(op, 4096, dt) == 1
+            assert P.rowops_path(op, 16384, dt) == 1 and P.rowops_path(op, 16392, dt) == 2
+            assert P.rowops_path(op, 1, dt) == 2 and P.rowops_path(op, 4095, dt) == 2 and P.rowops_path(op, 1 << 24, dt) == 2
+            assert P.rowops_path(op, 0, dt) == 0 and P.rowops_path(op, (1 << 24) + 8, dt) == 0
+        assert P.rowops_path(op, 64, 2) == 0
+    assert P.rowops_path(2, 64, 0) == 0
+
+
+def test_rowops_bad_arguments_rejected_without_a_gpu(P):
+    ok = 4096  # any non-null 16-byte aligned address: validation fails before it is touched
+    sm, rn = P.softmax_rows_fwd_raw, P.rmsnorm_fwd_raw
+    assert sm(0, ok, 4, 64, 0, 0) == -1 and sm(ok, 0, 4, 64, 0, 0) == -1
+    assert sm(ok, ok, -1, 64, 0, 0) == -2 and sm(ok, ok, 4, 0, 0, 0) == -2 and sm(ok, ok, 4, (1 << 24) + 1, 0, 0) == -2
+    assert sm(ok, ok, 1 << 30, 1 << 20, 0, 0) == -2
+    assert sm(ok, ok, 4, 64, 2, 0) == -3 and sm(ok, ok, 4, 64, -1, 0) == -3
+    assert sm(ok + 2, ok, 4, 64, 0, 0) == -6 and sm(ok, ok + 8, 4, 64, 0, 0) == -6
+    assert sm(0, 0, 0, 64, 0, 0) == 0          # an empty input is valid and launches nothing
+    assert rn(0, ok, ok, 4, 64, 1e-6, 0, 0) == -1 and rn(ok, 0, ok, 4, 64, 1e-6, 0, 0) == -1 and rn(ok, ok, 0, 4, 64, 1e-6, 0, 0) == -1
+    assert rn(ok, ok, ok, -2, 64, 1e-6, 0, 0) == -2 and rn(ok, ok, ok, 4, -64, 1e-6, 0, 0) == -2
+    assert rn(ok, ok, ok, 4, 64, 1e-6, 7, 0) == -3
+    assert rn(ok, ok, ok, 4, 64, -1e-6, 0, 0) == -4 and rn(ok, ok, ok, 4, 64, float("nan"), 0, 0) == -4
+    assert rn(ok, ok, ok, 4, 64, float("inf"), 0, 0) == -4
+    assert rn(ok, ok + 4, ok, 4, 64, 1e-6, 0, 0) == -6
+    assert rn(0, 0, 0, 0, 64, 1e-6, 0, 0) == 0
 
 
 def test_status_strings(P):
