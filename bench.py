@@ -32,21 +32,34 @@ TRAFFIC = {
 }
 
 
-def kernel_source_sha256(csrc):
+# the same for the row kernels (workload name as bench_rowop reports it)
+ROW_TRAFFIC = {
+    "softmax_512x4096_f16 x16 rows": {"fetch_kib": 32803.1 * 2.0, "write_kib": 65536.0 * 1.0,
+                                      "kernel_sha256": "efc90703c88cd78fc96c429b78ffe9d0151fd5461670fbd9a3e86f4f176ea240"},
+    "rmsnorm_1x32x4096x64_f16 x16 rows": {"fetch_kib": 131108.2 * 2.0, "write_kib": 262144.0 * 1.0,
+                                          "kernel_sha256": "efc90703c88cd78fc96c429b78ffe9d0151fd5461670fbd9a3e86f4f176ea240"},
+}
+
+
+def kernel_source_sha256(csrc, files=("attn_fwd_gfx950.hip", "attn_launch.h")):
     import hashlib
     h = hashlib.sha256()
-    for f in ("attn_fwd_gfx950.hip", "attn_launch.h"):
+    for f in files:
         h.update(open(os.path.join(csrc, f), "rb").read())
     return h.hexdigest()
 
 
 def measured_traffic(workload_name):
     t = TRAFFIC.get(workload_name)
+    files = ("attn_fwd_gfx950.hip", "attn_launch.h")
+    if t is None:
+        t = ROW_TRAFFIC.get(workload_name)
+        files = ("rowops_gfx950.hip", "rowops_launch.h")
     if t is None:
         return None
     csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2501_08071_amd", "csrc")
     try:
-        sha = kernel_source_sha256(csrc)
+        sha = kernel_source_sha256(csrc, files)
     except OSError:
         return None
     if sha != t["kernel_sha256"]:
@@ -79,8 +92,76 @@ def cpu_baseline(w, q, k, v, budget_s=15.0):
             "seconds": dt}
 
 
+def bench_rowop(args):
+    """The paper's memory-bound kernels (Table 2): one step = one launch over the whole matrix.  HBM roofline:
+    algorithmic bytes = every element read once and written once (plus the weight once)."""
+    import torch
+    import paper_2501_08071_amd as P
+    from paper_2501_08071_amd import inputs as I
+
+    name = {"softmax": "softmax_512x4096_f16", "rmsnorm": "rmsnorm_1x32x4096x64_f16"}[args.op]
+    op, n_rows, n, dt = I.ROWOP_SHAPES[name]
+    n_rows *= args.rows_mul
+    xb = I.gen_rows(n_rows, n, dt, tensor_id=0)
+    x = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.float16)
+    y = torch.empty_like(x)
+    stream = torch.cuda.current_stream()
+    if op == "softmax":
+        def step():
+            P.softmax_rows_fwd(x, y=y, stream=stream)
+        nbytes = 2 * 2 * n_rows * n
+    else:
+        wb = I.gen_rows(1, n, dt, tensor_id=1)[0]
+        wt = torch.from_numpy(wb.view(np.int16)).cuda().view(torch.float16)
+
+        def step():
+            P.rmsnorm_fwd(x, wt, 1e-6, y=y, stream=stream)
+        nbytes = 2 * 2 * n_rows * n + 2 * n
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    achieved = nbytes / (kern_ms * 1e-3) / 1e9
+    wname = name if args.rows_mul == 1 else f"{name} x{args.rows_mul} rows"
+    out = {
+        "metric": f"row {op} GB/s of algorithmic bytes (each element read once, written once) on 1 MI355X",
+        "value": nbytes * args.steps / wall / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wname, "n_rows": n_rows,
+                   "row_len": n, "io_dtype": "f16", "path": P.rowops_path(0 if op == "softmax" else 1, n, dt)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": 8000.0, "unit": "GB/s", "frac": achieved / 8000.0,
+                     "traffic": measured_traffic(wname), "traffic_unit": "bytes/launch", "algorithmic_bytes": nbytes,
+                     "kernel_ms": kern_ms},
+    }
+    if not args.no_cpu:
+        from oracle import rowops as R
+        m = min(n_rows, 4096 if op == "softmax" else 1 << 17)
+        t0 = time.perf_counter()
+        if op == "softmax":
+            R.softmax_rows(xb[:m], dt)
+        else:
+            R.rmsnorm_rows(xb[:m], wb, 1e-6, dt)
+        dtm = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2 * 2 * m * n / dtm / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {m} of {n_rows} rows, {dtm:.1f} s, fp64 numpy", "seconds": dtm}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--op", choices=["attn", "softmax", "rmsnorm"], default="attn",
+                    help="attn: the hot path (default); softmax, rmsnorm: the paper's memory-bound kernels at Table 2's shapes")
+    ap.add_argument("--rows-mul", type=int, default=1,
+                    help="softmax, rmsnorm: multiply the number of rows of the paper's shape (its own shape is a few MB)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=100)
@@ -106,6 +187,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.op != "attn":
+        bench_rowop(args)
+        return
     if args.calibrate_copy:
         # a plain copy kernel of known size: what FETCH_SIZE / WRITE_SIZE read for it scales those counters
         n = args.calibrate_copy << 20
