@@ -55,6 +55,13 @@ def _load() -> ctypes.CDLL:
     lib.rowops_path.restype = ctypes.c_int
     lib.rowops_status_str.argtypes = [ctypes.c_int]
     lib.rowops_status_str.restype = ctypes.c_char_p
+    # include/gemm.h
+    lib.gemm_leakyrelu_fwd.argtypes = [vp, vp, vp] + [ctypes.c_int] * 4 + [ctypes.c_float, ctypes.c_int, vp]
+    lib.gemm_leakyrelu_fwd.restype = ctypes.c_int
+    lib.gemm_path.argtypes = [ctypes.c_int] * 5
+    lib.gemm_path.restype = ctypes.c_int
+    lib.gemm_status_str.argtypes = [ctypes.c_int]
+    lib.gemm_status_str.restype = ctypes.c_char_p
     return lib
 
 
@@ -206,3 +213,56 @@ def rmsnorm_fwd(x, w, eps: float, y=None, stream=None):
     if rc != 0:
         raise RowopsError("rmsnorm_fwd", rc, rowops_status_str(rc))
     return y
+
+
+# ---- include/gemm.h --------------------------------------------------------------------------
+
+class GemmError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"gemm_leakyrelu_fwd failed with status {status}: {msg}")
+        self.status = status
+
+
+def gemm_status_str(status: int) -> str:
+    return lib.gemm_status_str(int(status)).decode()
+
+
+def gemm_path(batch: int, M: int, N: int, K: int, dtype: int) -> int:
+    return int(lib.gemm_path(int(batch), int(M), int(N), int(K), int(dtype)))
+
+
+def gemm_leakyrelu_fwd_raw(a_ptr, b_ptr, c_ptr, batch, M, N, K, slope, dtype, stream) -> int:
+    """The C entry point as is: device addresses as ints (0 = NULL), returns the status."""
+    return int(lib.gemm_leakyrelu_fwd(a_ptr or None, b_ptr or None, c_ptr or None, int(batch), int(M), int(N), int(K),
+                                      float(slope), int(dtype), stream or None))
+
+
+def gemm_leakyrelu_fwd(a, b, slope: float = 0.01, c=None, stream=None):
+    """gemm_leakyrelu_fwd on torch device tensors: a [batch, M, K] (or [M, K]), b [batch, K, N] (or [K, N])
+    of one 16-bit dtype; returns c [batch, M, N] (or [M, N]) in that dtype."""
+    if a.dtype == torch.float16:
+        dtype = F16
+    elif a.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("a and b must be float16 or bfloat16")
+    if b.dtype != a.dtype or a.dim() != b.dim() or a.dim() not in (2, 3):
+        raise TypeError("a and b must share one dtype and be both [M,K],[K,N] or both [batch,M,K],[batch,K,N]")
+    a3, b3 = (a, b) if a.dim() == 3 else (a[None], b[None])
+    if a3.shape[0] != b3.shape[0] or a3.shape[2] != b3.shape[1]:
+        raise ValueError("a must be [batch, M, K] and b [batch, K, N]")
+    for t in (a, b):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("a and b must be contiguous device tensors")
+    batch, M, K = a3.shape
+    N = b3.shape[2]
+    shape = (batch, M, N) if a.dim() == 3 else (M, N)
+    if c is None:
+        c = torch.empty(shape, dtype=a.dtype, device=a.device)
+    elif c.dtype != a.dtype or tuple(c.shape) != shape or not c.is_cuda or not c.is_contiguous():
+        raise ValueError("c must be a contiguous device tensor [batch, M, N] of the dtype of a")
+    st = (stream or torch.cuda.current_stream(a.device)).cuda_stream
+    rc = gemm_leakyrelu_fwd_raw(a.data_ptr(), b.data_ptr(), c.data_ptr(), batch, M, N, K, slope, dtype, st)
+    if rc != 0:
+        raise GemmError(rc, gemm_status_str(rc))
+    return c

@@ -1,0 +1,299 @@
+// Fused GEMM + LeakyReLU for gfx950 (the paper's mmLeakyReLu, Table 2): c = f(a b), a [M,K], b [K,N]
+// row-major, 16-bit in and out, fp32 accumulation.
+//
+// Matrix-core kernel (K % 32 == 0, N % 8 == 0):
+//   * a workgroup of four wavefronts (2 x 2) owns a 64 TM x 64 TN tile of c, a wavefront 32 TM x 32 TN of
+//     it as TM x TN accumulator blocks of v_mfma_f32_32x32x16; TM = TN = 2 (128 x 128) when that gives
+//     the chip enough tiles, else 1 (64 x 64);
+//   * computed transposed, c^T = b^T a^T: the first operand is a 32 x 16 piece of b^T, fetched from the
+//     row-major b tile in LDS with transposing reads (ds_read_b64_tr_b16), the second 16 contiguous bytes
+//     of a row of a; a lane then holds four consecutive n of one row m of c and stores 8 bytes;
+//   * K runs in steps of 32 through four LDS stages; tiles come straight from global memory into LDS
+//     (global_load_lds_dwordx4, 16 bytes per lane, 1 KiB of consecutive LDS per instruction), three
+//     stages ahead, with the bank-conflict swizzle applied to the global address of each lane;
+//   * rows past M repeat the last row and column chunks past N the last chunk (results masked at the
+//     store), so the loop has no edge cases.
+// Plain kernel (any shape): one thread per element of c, fp32 fused multiply-adds in the order of k.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+#include <utility>
+
+#include "gemm_launch.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define LDS_AS __attribute__((address_space(3)))
+
+template <int DT> struct Elem;
+template <> struct Elem<0> {  // IEEE binary16
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // round to nearest even
+        f32x2 x = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
+    }
+    static __device__ __forceinline__ float widen(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+};
+template <> struct Elem<1> {  // bfloat16
+    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // round to nearest even
+        f32x2 x = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+    }
+    static __device__ __forceinline__ float widen(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
+};
+
+// 4 x 16-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
+// the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4 of its group.
+__device__ __forceinline__ u32x2 lds_read_tr16(uint32_t addr) {
+    s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(uintptr_t)addr);
+    return __builtin_bit_cast(u32x2, t);
+}
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) { return *(const LDS_AS u32x4*)(uintptr_t)addr; }
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l
+// (lds_base wave-uniform).  Written as asm so that the compiler's wait-count insertion does not know
+// about the transfer (it would wait for all of them in front of every LDS read); the wait is explicit.
+__device__ __forceinline__ void lds_dma16(uint32_t lds_base, const void* gbase, uint32_t byte_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(byte_off), "s"(gbase) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+
+// XOR swizzle of the 16-byte chunk index within a row, by row length (chunks per row 4, 8, 16): rows
+// that a wavefront reads together land in different banks both for the 16-byte row reads and for
+// the transposing 8-byte reads.
+__device__ __forceinline__ constexpr int swz_a(int row) { return (row >> 2) & 3; }
+template <int CHUNKS>
+__device__ __forceinline__ constexpr int swz_b(int row) {
+    return CHUNKS == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
+                        : ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1));
+}
+
+__device__ __forceinline__ float leaky(float t, float slope) { return t >= 0.f ? t : slope * t; }
+
+extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+template <int DT, int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_lrelu_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                        uint16_t* __restrict__ C, int M, int N, int K, int tiles_m,
+                                                        int tiles_n, float slope) {
+    using E = Elem<DT>;
+    constexpr int BM = 64 * TM, BN = 64 * TN, NST = 4;
+    constexpr int A_TILE = BM * 64;          // BM rows of 32 elements
+    constexpr int B_ROWB = 2 * BN;           // bytes per row of the b tile
+    constexpr int B_TILE = 32 * B_ROWB;      // 32 rows (k) of BN elements
+    constexpr int STAGE = A_TILE + B_TILE;
+    constexpr int B_LPR = B_ROWB / 16;       // lanes (16-byte chunks) per row of the b tile
+    constexpr int B_RPI = 64 / B_LPR;        // rows per load instruction
+    constexpr int IPS = TM + TN;             // load instructions per stage and wavefront
+    static_assert(A_TILE / 1024 == 4 * TM && B_TILE / 1024 == 4 * TN, "four wavefronts share the loads evenly");
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave & 1, wn = wave >> 1;
+
+    const int bx = blockIdx.x;
+    const int tn_i = bx % tiles_n;
+    const int tm_i = (bx / tiles_n) % tiles_m;
+    const int bi = bx / (tiles_n * tiles_m);
+    const int m0 = tm_i * BM, n0 = tn_i * BN;
+    const uint16_t* Ab = A + ((size_t)bi * M + m0) * K;
+    const uint16_t* Bb = B + (size_t)bi * K * N + n0;
+    uint16_t* Cb = C + (size_t)bi * M * N;
+    const int nk = K / 32;
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)smem;
+
+    // ---- loads: byte offset of this lane's source chunk inside the tile's rows ----
+    uint32_t goff_a[TM], goff_b[TN];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int r = 16 * (wave * TM + j) + lane / 4, pos = lane % 4;
+        const int rr = r < M - 1 - m0 ? r : M - 1 - m0;
+        goff_a[j] = (uint32_t)(rr * K + ((pos ^ swz_a(r)) << 3)) * 2u;
+    }
+    {
+        const int nvalid = (N - n0) / 8 < BN / 8 ? (N - n0) / 8 : BN / 8;   // chunks of this tile inside the matrix
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int r = B_RPI * (wave * TN + j) + lane / B_LPR, pos = lane % B_LPR;
+            int ch = pos ^ swz_b<B_LPR>(r);
+            ch = ch < nvalid - 1 ? ch : nvalid - 1;
+            goff_b[j] = (uint32_t)(r * N + (ch << 3)) * 2u;
+        }
+    }
+    // k block kb into stage st; a block past the end repeats the last one (nobody reads it): every step
+    // issues the same number of loads and the wait count is a constant
+    auto issue = [&](int kb, int st) {
+        const int kc = kb < nk - 1 ? kb : nk - 1;
+        const uint16_t* sa = Ab + (size_t)kc * 32;
+        const uint16_t* sb = Bb + (size_t)kc * 32 * N;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) lds_dma16(lds0 + st * STAGE + (wave * TM + j) * 1024, sa, goff_a[j]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) lds_dma16(lds0 + st * STAGE + A_TILE + (wave * TN + j) * 1024, sb, goff_b[j]);
+    };
+
+    // ---- operand addresses (stage 0, k step 0 of the b tile) ----
+    uint32_t a_addr[TM][2];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+            a_addr[tm][ks] = lds0 + ((wm * TM + tm) * 32 + l32) * 64 + (((2 * ks + h) ^ swz_a(l32)) << 4);
+    // b^T operand: lane addresses 8 bytes of row (k) 8 h + 4 hi + x, elements (n) 16 g1 + 4 y .. +3 of the
+    // 32-wide block; the transposing read hands lane l the four k of element n = l % 32
+    uint32_t b_addr[2][TN];
+    {
+        const int x = (lane & 15) >> 2, y = lane & 3, g1 = (lane >> 4) & 1;
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int row = 8 * h + 4 * hi + x;
+                const int chunk = 4 * (wn * TN + tn) + 2 * g1 + (y >> 1);
+                b_addr[hi][tn] = lds0 + A_TILE + row * B_ROWB + ((chunk ^ swz_b<B_LPR>(row)) << 4) + ((y & 1) << 3);
+            }
+    }
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s, s);
+
+    auto step = [&](int kb, auto phase) {
+        constexpr int PH = decltype(phase)::value;
+        // k block kb has landed when at most the loads of the NST-2 later blocks are still out
+        wait_tile_loads<(NST - 2) * IPS>();
+        asm volatile("s_barrier" ::: "memory");
+        // ... for everybody, and everybody is done with block kb-1: its stage takes block kb+NST-1
+        issue(kb + NST - 1, (PH + NST - 1) % NST);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            u32x4 aop[TM], bop[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) aop[tm] = lds_read_b128(a_addr[tm][ks] + PH * STAGE);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const u32x2 lo = lds_read_tr16(b_addr[0][tn] + PH * STAGE + ks * 16 * B_ROWB);
+                const u32x2 hi = lds_read_tr16(b_addr[1][tn] + PH * STAGE + ks * 16 * B_ROWB);
+                bop[tn] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = E::mfma(bop[tn], aop[tm], acc[tn][tm]);
+        }
+    };
+    for (int k0 = 0; k0 < nk; k0 += NST) {
+        [&]<int... PH>(std::integer_sequence<int, PH...>) {
+            ((k0 + PH < nk ? step(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
+        }(std::make_integer_sequence<int, NST>{});
+    }
+    wait_tile_loads<0>();   // the repeated loads of the last steps must not outlive the workgroup's LDS
+
+    // ---- epilogue: activation in fp32, round, 8-byte stores ----
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int m = m0 + (wm * TM + tm) * 32 + l32;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                const int n = n0 + (wn * TN + tn) * 32 + 8 * gg + 4 * h;
+                const f32x16& t = acc[tn][tm];
+                const u32x2 v = {E::pack2(leaky(t[4 * gg], slope), leaky(t[4 * gg + 1], slope)),
+                                 E::pack2(leaky(t[4 * gg + 2], slope), leaky(t[4 * gg + 3], slope))};
+                if (m < M && n < N) *(u32x2*)(Cb + (size_t)m * N + n) = v;
+            }
+    }
+}
+
+// any shape: one thread per element of c
+template <int DT>
+__global__ __launch_bounds__(256) void gemm_lrelu_plain_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                              uint16_t* __restrict__ C, long long total, int M, int N, int K,
+                                                              float slope) {
+    using E = Elem<DT>;
+    for (long long idx = (long long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long long)gridDim.x * 256) {
+        const int n = (int)(idx % N);
+        const long long bm = idx / N;          // batch * M + m
+        const long long bi = bm / M;
+        const uint16_t* a = A + (size_t)bm * K;
+        const uint16_t* b = B + (size_t)bi * K * N + n;
+        float t = 0.f;
+        for (int k = 0; k < K; ++k) t = __builtin_fmaf(E::widen(a[k]), E::widen(b[(size_t)k * N]), t);
+        const uint32_t p = E::pack2(leaky(t, slope), 0.f);
+        C[idx] = (uint16_t)(p & 0xFFFFu);
+    }
+}
+
+template <int DT, int TM, int TN>
+hipError_t launch_tiles(const GemmLaunch& g) {
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr unsigned lds_bytes = 4u * (BM * 64 + 32 * 2 * BN);
+    int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const long long blocks = (long long)tiles_m * tiles_n * g.batch;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const uint16_t* a = (const uint16_t*)g.a;
+    const uint16_t* b = (const uint16_t*)g.b;
+    uint16_t* c = (uint16_t*)g.c;
+    int M = g.M, N = g.N, K = g.K;
+    float slope = g.slope;
+    void* args[] = {&a, &b, &c, &M, &N, &K, &tiles_m, &tiles_n, &slope};
+    const void* fn = reinterpret_cast<const void*>(&gemm_lrelu_kernel<DT, TM, TN>);
+    static_assert(lds_bytes <= 65536u, "within the default dynamic LDS limit");
+    return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(256), args, lds_bytes, (hipStream_t)g.stream);
+}
+
+template <int DT>
+hipError_t launch_plain(const GemmLaunch& g) {
+    const uint16_t* a = (const uint16_t*)g.a;
+    const uint16_t* b = (const uint16_t*)g.b;
+    uint16_t* c = (uint16_t*)g.c;
+    long long total = (long long)g.batch * g.M * g.N;
+    int M = g.M, N = g.N, K = g.K;
+    float slope = g.slope;
+    const long long groups = (total + 255) / 256;
+    const unsigned grid = (unsigned)(groups < 65536 ? groups : 65536);
+    void* args[] = {&a, &b, &c, &total, &M, &N, &K, &slope};
+    return hipLaunchKernel(reinterpret_cast<const void*>(&gemm_lrelu_plain_kernel<DT>), dim3(grid), dim3(256), args, 0,
+                           (hipStream_t)g.stream);
+}
+
+template <int DT>
+hipError_t dispatch(const GemmLaunch& g) {
+    switch (gemm_path_of(g.batch, g.M, g.N, g.K)) {
+        case 1: return launch_tiles<DT, 2, 2>(g);
+        case 2: return launch_tiles<DT, 1, 1>(g);
+        default: return launch_plain<DT>(g);
+    }
+}
+
+}  // namespace
+
+hipError_t gemm_launch(const GemmLaunch& g) { return g.dtype == 0 ? dispatch<0>(g) : dispatch<1>(g); }

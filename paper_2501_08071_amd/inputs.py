@@ -200,3 +200,15 @@ def gen_rows(n_rows: int, n_cols: int, dtype: int, *, tensor_id: int = 0, seed: 
              dist: str = "normal", mul: float = 1.0) -> np.ndarray:
     """A seeded [n_rows, n_cols] matrix of 16-bit patterns (tensor_id separates x from the weight)."""
     return _fill(tensor_seed(seed, 100, tensor_id), n_rows * n_cols, dist, mul, dtype).reshape(n_rows, n_cols)
+
+
+GEMM_SHAPES = {
+    "mmLeakyReLu_1x512x512x2048_f16": (1, 512, 512, 2048, F16),      # B, M, N, K (Table 2)
+}
+
+
+def gen_gemm(batch: int, M: int, N: int, K: int, dtype: int, *, seed: int = BASE_SEED):
+    """Seeded a [batch, M, K] and b [batch, K, N] as 16-bit patterns, entries N(0,1)."""
+    a = _fill(tensor_seed(seed, 200, 0), batch * M * K, "normal", 1.0, dtype).reshape(batch, M, K)
+    b = _fill(tensor_seed(seed, 200, 1), batch * K * N, "normal", 1.0, dtype).reshape(batch, K, N)
+    return a, b

@@ -37,7 +37,35 @@ def test_every_declared_symbol_is_exported(P):
     assert names == ["rmsnorm_fwd", "rowops_path", "rowops_status_str", "softmax_rows_fwd"]
     for n in names:
         assert hasattr(P.lib, n), f"{n} is declared in rowops.h but not exported"
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["attn.h", "rowops.h"]
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "gemm.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(gemm_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["gemm_leakyrelu_fwd", "gemm_path", "gemm_status_str"]
+    for n in names:
+        assert hasattr(P.lib, n), f"{n} is declared in gemm.h but not exported"
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["attn.h", "gemm.h", "rowops.h"]
+
+
+def test_gemm_paths_status_and_bad_arguments(P):
+    seen = {P.gemm_status_str(st) for st in (0, -1, -2, -3, -4, -6, -7)}
+    assert len(seen) == 7 and "unknown status" not in seen and P.gemm_status_str(-5) == "unknown status"
+    for dt in (0, 1):
+        assert P.gemm_path(1, 512, 512, 2048, dt) == 2           # the paper's shape: 16 large tiles would leave the chip idle
+        assert P.gemm_path(1, 4096, 4096, 4096, dt) == 1 and P.gemm_path(4, 1024, 1024, 64, dt) == 1
+        assert P.gemm_path(1, 64, 64, 48, dt) == 3 and P.gemm_path(1, 64, 12, 64, dt) == 3 and P.gemm_path(1, 8, 8, 0, dt) == 3
+        assert P.gemm_path(1, 8, 8, 1 << 23, dt) == 3
+        assert P.gemm_path(0, 0, 0, 0, dt) == 3                  # valid and empty
+        assert P.gemm_path(-1, 8, 8, 8, dt) == 0 and P.gemm_path(1, 1 << 20, 8, 1 << 20, dt) == 0
+    assert P.gemm_path(1, 8, 8, 32, 2) == 0
+    ok = 4096
+    f = P.gemm_leakyrelu_fwd_raw
+    assert f(0, ok, ok, 1, 8, 8, 32, 0.01, 0, 0) == -1 and f(ok, 0, ok, 1, 8, 8, 32, 0.01, 0, 0) == -1
+    assert f(ok, ok, 0, 1, 8, 8, 32, 0.01, 0, 0) == -1 and f(0, 0, 0, 1, 8, 8, 0, 0.01, 0, 0) == -1
+    assert f(ok, ok, ok, -1, 8, 8, 32, 0.01, 0, 0) == -2 and f(ok, ok, ok, 1, 8, -8, 32, 0.01, 0, 0) == -2
+    assert f(ok, ok, ok, 1, 1 << 16, 8, 1 << 16, 0.01, 0, 0) == -2 and f(ok, ok, ok, 70000, 8, 8, 32, 0.01, 0, 0) == -2
+    assert f(ok, ok, ok, 1, 8, 8, 32, 0.01, 5, 0) == -3
+    assert f(ok, ok, ok, 1, 8, 8, 32, float("inf"), 0, 0) == -4 and f(ok, ok, ok, 1, 8, 8, 32, float("nan"), 0, 0) == -4
+    assert f(ok + 8, ok, ok, 1, 8, 8, 32, 0.01, 0, 0) == -6 and f(ok, ok, ok + 2, 1, 8, 8, 32, 0.01, 0, 0) == -6
+    assert f(0, 0, 0, 0, 8, 8, 32, 0.01, 0, 0) == 0 and f(0, 0, 0, 1, 0, 8, 32, 0.01, 0, 0) == 0 and f(0, 0, 0, 1, 8, 0, 32, 0.01, 0, 0) == 0
 
 
 def test_rowops_status_strings_and_paths(P):
