@@ -156,10 +156,71 @@ def bench_rowop(args):
     print(json.dumps(out))
 
 
+def bench_gemm(args):
+    """The paper's fused GEMM + LeakyReLU (Table 2: B, M, N, K = 1, 512, 512, 2048, float16), or a square one of
+    --gemm-size.  MFMA roofline: 2 M N K flops per launch."""
+    import torch
+    import paper_2501_08071_amd as P
+    from paper_2501_08071_amd import inputs as I
+
+    if args.gemm_size:
+        name = f"mmLeakyReLu_1x{args.gemm_size}x{args.gemm_size}x{args.gemm_size}_f16"
+        batch, M, N, K, dt = 1, args.gemm_size, args.gemm_size, args.gemm_size, I.F16
+    else:
+        name = "mmLeakyReLu_1x512x512x2048_f16"
+        batch, M, N, K, dt = I.GEMM_SHAPES[name]
+    ab, bb = I.gen_gemm(batch, M, N, K, dt)
+    a = torch.from_numpy(ab.view(np.int16)).cuda().view(torch.float16)
+    b = torch.from_numpy(bb.view(np.int16)).cuda().view(torch.float16)
+    c = torch.empty((batch, M, N), dtype=torch.float16, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        P.gemm_leakyrelu_fwd(a, b, 0.01, c=c, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = ev0.elapsed_time(ev1) / args.steps
+    flops = 2.0 * batch * M * N * K
+    achieved = flops / (kern_ms * 1e-3) / 1e12
+    out = {
+        "metric": "fused GEMM + LeakyReLU TFLOP/s (2 M N K flops) on 1 MI355X",
+        "value": flops * args.steps / wall / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": name, "batch": batch, "M": M, "N": N, "K": K, "slope": 0.01,
+                   "path": P.gemm_path(batch, M, N, K, dt)},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_TFLOPS["f16"], "traffic": None, "traffic_unit": "bytes/launch",
+                     "algorithmic_bytes": 2 * batch * (M * K + K * N + M * N), "kernel_ms": kern_ms},
+    }
+    if not args.no_cpu:
+        from oracle import gemm as G
+        m = min(M, 256)
+        t0 = time.perf_counter()
+        G.gemm_leakyrelu(ab[:, :m], bb, 0.01, dt)
+        dtm = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * batch * m * N * K / dtm / 1e12, "unit": "TFLOP/s", "cores": os.cpu_count(),
+                               "kind": "oracle", "sample": f"the first {m} of {M} rows of a, {dtm:.2f} s, fp64 numpy matmul",
+                               "seconds": dtm}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", choices=["attn", "softmax", "rmsnorm"], default="attn",
-                    help="attn: the hot path (default); softmax, rmsnorm: the paper's memory-bound kernels at Table 2's shapes")
+    ap.add_argument("--op", choices=["attn", "softmax", "rmsnorm", "gemm"], default="attn",
+                    help="attn: the hot path (default); softmax, rmsnorm, gemm: the paper's memory-bound kernels and its "
+                         "fused GEMM + LeakyReLU at Table 2's shapes")
+    ap.add_argument("--gemm-size", type=int, default=0, help="gemm: a square problem M = N = K of this size instead of Table 2's")
     ap.add_argument("--rows-mul", type=int, default=1,
                     help="softmax, rmsnorm: multiply the number of rows of the paper's shape (its own shape is a few MB)")
     ap.add_argument("--gpus", type=int, default=1)
@@ -187,6 +248,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.op == "gemm":
+        bench_gemm(args)
+        return
     if args.op != "attn":
         bench_rowop(args)
         return
