@@ -46,7 +46,7 @@ extern "C" int attn_tile_rows(int D, int dtype, int causal) {
 }
 
 extern "C" int attn_tile_keys(int D, int dtype, int causal) {
-    return attn_supported(1, D, dtype, causal) ? ATTN_BC : 0;
+    return attn_supported(1, D, dtype, causal) ? attn_block_keys(D) : 0;
 }
 
 namespace {

@@ -7,21 +7,23 @@
 //
 // Work split
 //   workgroup = NW wavefronts, each owning 32 consecutive query rows of one (b,h);
-//   K/V stream through LDS in blocks of BC = 32 keys shared by the whole workgroup.
+//   K/V stream through LDS in blocks of BC keys shared by the whole workgroup (64 in the
+//   alternating-phase loop, 32 in the interleaved one).
 //
 // K/V movement
-//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), ATTN_NBUF buffers per tensor,
-//   loads issued about ATTN_NBUF blocks ahead of their use.  Such a load writes 1 KiB of consecutive
+//   global -> LDS directly (global_load_lds_dwordx4, no VGPR staging), ATTN_NBUF buffers of 32 keys per
+//   tensor (half as many of 64), loads issued about that many blocks ahead of their use.  Such a load writes 1 KiB of consecutive
 //   LDS per wavefront, so rows cannot be padded; bank conflicts are avoided by an XOR swizzle of the
 //   16-byte chunk index within each row, applied on the global-address side.
 //
 // Schedule
 //   The two wavefronts of a SIMD share one issue port for vector and matrix instructions, and the
-//   vector work of a key block (16 fma, 16 exp, 16 add, 8 convert per lane) is of the order of its
+//   vector work of 32 keys (16 fma, 16 exp, 16 add, 8 convert per lane) is of the order of their
 //   matrix work (16 matrix instructions at D = 128, 8 at D = 64).  Two loop structures:
 //   D = 128  two groups of wavefronts run matrix phases M(k): S(k) = K(k).Q^T, O += V(k-1)^T.P(k-1)^T
 //            and vector phases V(k): P(k) = exp2(c S(k) - m) half a block apart, a barrier between
 //            phases: on every SIMD one wavefront feeds the matrix pipe while the other has the vector port;
+//            64 keys per block, so that a phase is 32 matrix instructions long;
 //   D = 64   every wavefront interleaves the matrix instructions of S(k+1) and O += V(k-1)^T.P(k-1)^T
 //            with the vector work of P(k); one barrier per two blocks.
 //   The softmax reference m of a row is the maximum of its first block; it is only taken again when a
@@ -148,14 +150,17 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                      uint32_t qsign, int o16) {
     using E = Elem<DT>;
     constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
-    constexpr int BC = ATTN_BC;        // keys per block
-    constexpr int NBUF = ATTN_NBUF;    // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
+    // keys per block: 32, or 64 in the alternating-phase loop (a phase then has twice the work between its
+    // two barriers; half as many buffers of twice the size)
+    constexpr int BC = attn_block_keys(D);
+    constexpr int NSUB = BC / 32;      // 32-key sub-blocks (one accumulator tile of S each)
+    constexpr int NBUF = attn_buffers(D);   // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
     // Two loop structures (see below): D = 128 alternates matrix and vector phases between two groups
     // of wavefronts; D = 64, where the vector work outweighs the matrix work, interleaves both in every
     // wavefront.
     constexpr bool PP = ATTN_PINGPONG != 0 && D == 128;
     constexpr int BEV = ATTN_BARRIER_EVERY;    // interleaved loop: slots per workgroup barrier (1 or 2)
-    static_assert((BEV == 1 || BEV == 2) && ATTN_NBUF % BEV == 0, "barrier period");
+    static_assert((BEV == 1 || BEV == 2) && NBUF % BEV == 0, "barrier period");
     // block k's step issues the load of K(k + KAHEAD) and of V(k + VAHEAD), into buffers nobody reads
     // any more (last read before the previous barrier, by either group)
     constexpr int KAHEAD = PP ? NBUF - 1 : NBUF - (BEV - 1);
@@ -170,7 +175,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int IPT = BC / RPI;      // such instructions per block and tensor
     constexpr int IPW = IPT >= NW ? IPT / NW : 1;   // ... per loading wavefront
     constexpr int LOADERS = IPT / IPW;              // wavefronts that issue loads
-    static_assert(BC == 32 && IPT % IPW == 0 && LOADERS <= NW, "load split");
+    static_assert((BC == 32 || (PP && BC == 64)) && IPT % IPW == 0 && LOADERS <= NW, "load split");
     // LDS: K buffers 0..NBUF-1 | V buffers 0..NBUF-1
 
     const float c = c_arg;
@@ -219,7 +224,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // workgroup are masked entirely for it.
     const int nfull = S / BC;
     auto first_masked = [&](int w) {
-        const int d = CAUSAL ? q0 / BC + w : nfull;
+        const int d = CAUSAL ? (q0 + 32 * w) / BC : nfull;
         return d < nfull ? d : nfull;
     };
     const int kd = first_masked(wave);
@@ -316,7 +321,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
     }
 
-    constexpr int NU = KSTEPS + 2 * DB;   // units (operand fetches) per slot
+    constexpr int NT = BC / 16;                      // 16-key steps of the second product
+    constexpr int NU = NSUB * KSTEPS + NT * DB;      // matrix instructions (units, operand fetches) per block
     auto fetch_v = [&](int VB, int tt, int i) {
         u32x2 lo = lds_read_tr16(vaddr[0][i] + VB * BLKB + 16 * tt * ROWB);
         u32x2 hi = lds_read_tr16(vaddr[1][i] + VB * BLKB + 16 * tt * ROWB);
@@ -346,8 +352,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         // first operands of the next matrix phase, read before its barrier
         constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
         u32x4 pre[FETCH];
-        f32x16 s;        // S(k): written by M(k), read by V(k)
-        u32x4 pf[2];     // weights of block k-1 (matrix operand layout) for M(k)
+        f32x16 s[NSUB];  // S(k): written by M(k), read by V(k)
+        u32x4 pf[NT];    // weights of block k-1 (matrix operand layout) for M(k)
 
         // Two groups of wavefronts (0 .. NW/2-1 and NW/2 .. NW-1; wavefront w and w + NW/2 share a SIMD) run
         // the same sequence of phases half a block apart: while one group is in its matrix phase M(k) --
@@ -362,20 +368,23 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             u32x4 opnd[NU];
             auto fetch = [&](auto unit) {
                 constexpr int U = decltype(unit)::value;
-                if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
-                else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
+                constexpr int NQK = NSUB * KSTEPS;
+                if constexpr (U < NQK) opnd[U] = lds_read_b128(kaddr[U % KSTEPS] + KB * BLKB + (U / KSTEPS) * 32 * ROWB);
+                else opnd[U] = fetch_v(VB, (U - NQK) / DB, (U - NQK) % DB);
             };
             auto unit_step = [&](auto unit) {
                 constexpr int U = decltype(unit)::value;
+                constexpr int NQK = NSUB * KSTEPS;
                 if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
-                if constexpr (U < KSTEPS) {
-                    if constexpr (U == 0) {
+                if constexpr (U < NQK) {
+                    constexpr int sub = U / KSTEPS, ks = U % KSTEPS;
+                    if constexpr (ks == 0) {
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+                        for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
                     }
-                    s = E::mfma(opnd[U], qf[U], s);
+                    s[sub] = E::mfma(opnd[U], qf[ks], s[sub]);
                 } else {
-                    constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
+                    constexpr int tt = (U - NQK) / DB, i = (U - NQK) % DB;
                     acc_o[i] = E::mfma(opnd[U], pf[tt], acc_o[i]);
                 }
                 // the 2 IPW load instructions of this block, evenly spread
@@ -402,32 +411,44 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                 // exact 0); past the diagonal that is all of them and the phase changes nothing.
                 const int lim = (CAUSAL ? qrow_ld : S - 1) - kb * BC - 4 * h;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int off = 8 * (r / 4) + (r % 4);
-                    s[r] = off > lim ? -3.0e38f : s[r];
-                }
+                for (int sub = 0; sub < NSUB; ++sub)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int off = 32 * sub + 8 * (r / 4) + (r % 4);
+                        s[sub][r] = off > lim ? -3.0e38f : s[sub][r];
+                    }
             }
             float psum = 0.f;
-            f32x16 p;
             auto weights = [&](float nm) {
                 psum = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c, nm));
-                    if (r % 2 == 1) {
-                        const uint32_t w = E::pack2(p[r - 1], p[r]);
-                        pf[r / 8][(r % 8) / 2] = w;
-                        if (DT == 0) psum = E::dot2_ones(w, psum);
+                for (int sub = 0; sub < NSUB; ++sub) {
+                    f32x16 p;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        p[r] = __builtin_amdgcn_exp2f(fmaf(s[sub][r], c, nm));
+                        if (r % 2 == 1) {
+                            const uint32_t w = E::pack2(p[r - 1], p[r]);
+                            pf[2 * sub + r / 8][(r % 8) / 2] = w;
+                            // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
+                            // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
+                            if (DT == 0) psum = E::dot2_ones(w, psum);
+                        }
+                        if (DT == 1) psum += p[r];
                     }
-                    if (DT == 1) psum += p[r];
                 }
             };
             if (kb != 0) weights(-m_ref);
             if (kb == 0 || __builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0) {
-                float mx = vmax3(s[0], s[1], s[2]);
+                float mx = vmax3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
-                for (int j = 1; j < 7; ++j) mx = vmax3(mx, s[2 * j + 1], s[2 * j + 2]);
-                mx = vmax(mx, s[15]);
+                for (int j = 1; j < 7; ++j) mx = vmax3(mx, s[0][2 * j + 1], s[0][2 * j + 2]);
+                mx = vmax(mx, s[0][15]);
+#pragma unroll
+                for (int sub = 1; sub < NSUB; ++sub) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) mx = vmax3(mx, s[sub][2 * j], s[sub][2 * j + 1]);
+                }
                 const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
                 const float m_new = m > m_ref ? m : m_ref;
                 const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -442,7 +463,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         };
 
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) pf[tt] = u32x4{0u, 0u, 0u, 0u};
+        for (int tt = 0; tt < NT; ++tt) pf[tt] = u32x4{0u, 0u, 0u, 0u};
         m_ref = -INFINITY;
         const bool grp1 = wave >= NW / 2;
         // prologue: K(0), the first load, has to be there for the first operand reads
@@ -452,12 +473,16 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u]);
         if (grp1) asm volatile("s_barrier" ::: "memory");   // the second group starts half a block late
 
-        // In the order of issue K(j) is load number 2 j (K(0) number 1) and V(j) number 2 j + 3; before M(k),
-        // KAHEAD + VAHEAD + 2 k are out.  Every wavefront makes sure of its own share of K(k+2) and V(k+1)
-        // before the barrier in front of its M(k): that is one block more than it needs itself, for the
-        // other group, whose last such check lies half a block back.
+        // In the order of issue K(j) is load number 2 j (K(0) number 1) and V(j) number 2 j + 3 (times IPW
+        // pieces); before M(k), KAHEAD + VAHEAD + 2 k are out.  The barriers alternate: first group into M(k),
+        // second group into M(k) (= first group into V(k)), ...  M(k) reads K(k) and V(k-1), V(k) reads the
+        // first operands of K(k+1).  A wavefront's check stands in front of its own M(k); what the other group
+        // starts one barrier later must be covered by it as well: the first group's V(k) needs K(k+1), the
+        // first group's M(k+1) needs K(k+1) and V(k) from the second group's check.  So every wavefront makes
+        // sure of its share of K(k+1) and V(k), load number 2 k + 3: all but the last KAHEAD + VAHEAD - 3.
+        constexpr int IN_FLIGHT = (KAHEAD + VAHEAD - 3) * IPW;
         auto block = [&](int kb, auto phase) {
-            wait_block_loads<(KAHEAD + VAHEAD - 5) * IPW>();
+            wait_block_loads<IN_FLIGHT>();
             asm volatile("s_barrier" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
             m_phase(kb, phase);
@@ -468,13 +493,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         };
         // The second product of a wavefront's last block, all operand reads first.
         auto closing_product = [&](int VB) {
-            u32x4 a[2][DB];
+            u32x4 a[NT][DB];
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
+            for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
                 for (int i = 0; i < DB; ++i) a[tt][i] = fetch_v(VB, tt, i);
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
+            for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
                 for (int i = 0; i < DB; ++i) acc_o[i] = E::mfma(a[tt][i], pf[tt], acc_o[i]);
         };
@@ -488,7 +513,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }(std::make_integer_sequence<int, NBUF>{});
         }
         for (int kb = last_w + 1; kb <= last_max; ++kb) {
-            wait_block_loads<(KAHEAD + VAHEAD - 5) * IPW>();
+            wait_block_loads<IN_FLIGHT>();
             asm volatile("s_barrier" ::: "memory");
             if (kb == last_w + 1) closing_product(last_w & (NBUF - 1));
 #pragma unroll
@@ -748,7 +773,7 @@ hipError_t launch(const AttnLaunch& a) {
     // the launch status is taken from the call itself: the thread's "last error" may hold a stale
     // value left by an unrelated earlier runtime call of the host program
     // NBUF K and NBUF V block buffers, and 4 KB per wavefront for the way out of the output tile
-    constexpr unsigned lds_bytes = 2u * ATTN_NBUF * ATTN_BC * 2u * D + NW * 4096u;
+    constexpr unsigned lds_bytes = 2u * attn_buffers(D) * attn_block_keys(D) * 2u * D + NW * 4096u;
     const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>);
     if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
         static bool raised = false;

@@ -6,7 +6,10 @@
 #ifndef ATTN_NW
 #define ATTN_NW 8   // wavefronts per workgroup, each owning 32 query rows
 #endif
-#define ATTN_BC 32  // keys per inner-loop block
+#ifndef ATTN_PP_KEYS
+#define ATTN_PP_KEYS 64   // keys per inner-loop block in the alternating-phase loop (32 or 64)
+#endif
+#define ATTN_BC 32  // keys per inner-loop block in the interleaved loop
 #ifndef ATTN_MAX_SLACK
 #define ATTN_MAX_SLACK 15.0f  // log2 of the largest sum of 16 softmax weights tolerated before the reference maximum is moved
 #endif
@@ -28,6 +31,13 @@
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif
+
+// Which loop a head dimension runs, the keys per inner-loop block and the LDS buffers per tensor that go with it.
+constexpr bool attn_alternating(int D) { return ATTN_PINGPONG != 0 && D == 128; }
+constexpr int attn_block_keys(int D) { return attn_alternating(D) ? ATTN_PP_KEYS : ATTN_BC; }
+constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 ? ATTN_NBUF / 2 : ATTN_NBUF; }
+
+static_assert(ATTN_PP_KEYS == 32 || ATTN_PP_KEYS == 64, "block size of the alternating-phase loop");
 
 struct AttnLaunch {
     const void* q;

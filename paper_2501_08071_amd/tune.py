@@ -7,7 +7,8 @@ the mean of 100 launches after 100 warm-up launches; Section 4: the best schedul
 GPU type and kernel configuration).  The paper searches with a reinforcement-learning agent over
 single-instruction moves of NVIDIA machine code.  Here the moves are the schedule decisions this kernel
 exposes at compile time -- how the matrix and vector work of the two wavefronts of a SIMD share the
-time, how often the workgroup synchronises, how far ahead operands and blocks are requested -- the
+time, how often the workgroup synchronises, how far ahead operands and blocks are requested, how much work
+lies between two barriers -- the
 search is exhaustive over the neighbours of the current state and greedy, so it is reproducible, and
 every candidate's output is compared with that of the shipped library on the same inputs before it is
 timed (the paper validates mutated schedules the same way, against the original schedule's output on
@@ -38,16 +39,20 @@ KNOBS: Dict[str, Tuple[str, Tuple[int, ...]]] = {
     "barrier_every": ("ATTN_BARRIER_EVERY", (1, 2)),  # interleaved loop: key blocks per workgroup barrier
     "fetch": ("ATTN_FETCH", (2, 4, 6)),             # matrix instructions between an LDS operand read and its use
     "nbuf": ("ATTN_NBUF", (4, 8)),                  # LDS buffers per tensor = how far ahead blocks are requested
+    "block": ("ATTN_PP_KEYS", (32, 64)),            # D = 128, alternating phases: keys per block = work between two barriers
 }
 State = Tuple[int, ...]                             # one value per knob, in KNOBS order
-START: State = (0, 1, 2, 4)                         # the plainest schedule: everything interleaved, nothing far ahead
+START: State = (0, 1, 2, 4, 32)                     # the plainest schedule: everything interleaved, nothing far ahead
 NOISE_PCT = 1.0                                     # two measurements of one schedule agree within about 1 % (Section 3.6)
 
 
 def valid(s: State) -> bool:
-    """Four buffers cannot hold what two key blocks between barriers need in flight."""
+    """Four buffers cannot hold what two key blocks between barriers need in flight; blocks of 64 keys exist
+    only in the alternating-phase loop and halve the number of buffers, which then has to be eight."""
     d = dict(zip(KNOBS, s))
-    return not (d["nbuf"] == 4 and d["barrier_every"] == 2)
+    if d["nbuf"] == 4 and d["barrier_every"] == 2:
+        return False
+    return d["block"] == 32 or (d["pingpong"] == 1 and d["nbuf"] == 8)
 
 
 def all_states() -> List[State]:

@@ -8,14 +8,19 @@ from paper_2501_08071_amd import tune
 
 def test_grid_and_moves():
     states = tune.all_states()
-    assert len(states) == len(set(states)) == 18
+    assert len(states) == len(set(states)) == 24
     assert tune.START in states and all(tune.valid(s) for s in states)
     for s in states:
         for n in tune.neighbours(s):
             assert n in states and sum(a != b for a, b in zip(s, n)) == 1      # one knob, one step
             assert s in tune.neighbours(n)                                      # every move can be taken back
-    assert set(tune.neighbours(tune.START)) == {(1, 1, 2, 4), (0, 1, 4, 4), (0, 1, 2, 8)}   # (0,2,2,4) is not valid
-    assert tune.state_flags((1, 2, 4, 8)) == ["-DATTN_PINGPONG=1", "-DATTN_BARRIER_EVERY=2", "-DATTN_FETCH=4", "-DATTN_NBUF=8"]
+    # (0,2,2,4,32) is not valid (two blocks between barriers need eight buffers), nor is (0,1,2,4,64) (blocks of
+    # 64 keys exist in the alternating-phase loop only)
+    assert set(tune.neighbours(tune.START)) == {(1, 1, 2, 4, 32), (0, 1, 4, 4, 32), (0, 1, 2, 8, 32)}
+    assert set(tune.neighbours((1, 1, 2, 8, 32))) == {(0, 1, 2, 8, 32), (1, 2, 2, 8, 32), (1, 1, 4, 8, 32), (1, 1, 2, 4, 32),
+                                                      (1, 1, 2, 8, 64)}
+    assert tune.state_flags((1, 2, 4, 8, 64)) == ["-DATTN_PINGPONG=1", "-DATTN_BARRIER_EVERY=2", "-DATTN_FETCH=4", "-DATTN_NBUF=8",
+                                                  "-DATTN_PP_KEYS=64"]
 
 
 def test_reward_is_the_papers():
@@ -38,14 +43,15 @@ def test_greedy_play_takes_the_biggest_gain_first_and_stops_at_the_noise():
         return _separable(s)
 
     r = tune.play_game(timer)
-    assert [m["to"] for m in r["moves"]] == ["pingpong1_barrier_every1_fetch2_nbuf4", "pingpong1_barrier_every1_fetch2_nbuf8",
-                                             "pingpong1_barrier_every1_fetch4_nbuf8", "pingpong1_barrier_every2_fetch4_nbuf8"]
+    assert [m["to"] for m in r["moves"]] == ["pingpong1_barrier_every1_fetch2_nbuf4_block32", "pingpong1_barrier_every1_fetch2_nbuf8_block32",
+                                             "pingpong1_barrier_every1_fetch4_nbuf8_block32",
+                                             "pingpong1_barrier_every2_fetch4_nbuf8_block32"]
     assert [round(m["reward"], 6) for m in r["moves"]] == [20.0, 10.0, 5.0, 2.0]
     assert r["total_reward"] == pytest.approx(37.0) and r["speedup"] == pytest.approx(1 / 0.63)
     assert len(calls) == len(set(calls))                # no schedule is measured twice
     # with a noise floor above the smallest gain the last move is not taken
     r2 = tune.play_game(_separable, noise_pct=3.0)
-    assert r2["final"] == "pingpong1_barrier_every1_fetch4_nbuf8"
+    assert r2["final"] == "pingpong1_barrier_every1_fetch4_nbuf8_block32"
     # deterministic: same timer, same trajectory
     assert tune.play_game(_separable)["moves"] == r["moves"]
 
