@@ -25,10 +25,10 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X published dense matrix 
 # only for the kernel source they were taken with (sha256 over the kernel and its configuration header),
 # otherwise reported as null.
 TRAFFIC = {
-    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 153292 * 2.0, "write_kib": 132096 * 1.0,
-                                      "kernel_sha256": "d03b8df2a2e6efa91ffbe6f1527bc0a82dd29cf65018df34d06c90c1aa238c9a"},
-    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 747435 * 2.0, "write_kib": 264192 * 1.0,
-                                       "kernel_sha256": "d03b8df2a2e6efa91ffbe6f1527bc0a82dd29cf65018df34d06c90c1aa238c9a"},
+    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 154696 * 2.0, "write_kib": 132096 * 1.0,
+                                      "kernel_sha256": "757d08a49eb695061c0501354316b006311e24b497b4ca6f4d52845abdcd7102"},
+    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 928836 * 2.0, "write_kib": 264192 * 1.0,
+                                       "kernel_sha256": "757d08a49eb695061c0501354316b006311e24b497b4ca6f4d52845abdcd7102"},
 }
 
 
