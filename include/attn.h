@@ -95,6 +95,13 @@ const char *attn_kernel_name(int S, int D, int dtype, int causal);
 int attn_tile_rows(int D, int dtype, int causal);
 int attn_tile_keys(int D, int dtype, int causal);
 
+/*
+ * Query rows per workgroup attn_fwd uses for this very problem: attn_tile_rows, or half of it (the
+ * same kernel with half the wavefronts, "..., 4>" in its name) when the problem has so few tiles
+ * that the larger ones would leave half of the chip idle.  0 if unsupported.
+ */
+int attn_launch_rows(int B, int H, int S, int D, int dtype, int causal);
+
 #ifdef __cplusplus
 }
 #endif

@@ -46,6 +46,8 @@ def _load() -> ctypes.CDLL:
     for f in (lib.attn_tile_rows, lib.attn_tile_keys):
         f.argtypes = [ctypes.c_int] * 3
         f.restype = ctypes.c_int
+    lib.attn_launch_rows.argtypes = [ctypes.c_int] * 6
+    lib.attn_launch_rows.restype = ctypes.c_int
     # include/rowops.h
     lib.softmax_rows_fwd.argtypes = [vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.softmax_rows_fwd.restype = ctypes.c_int
@@ -87,6 +89,10 @@ def attn_tile_rows(D: int, dtype: int, causal: bool) -> int:
 
 def attn_tile_keys(D: int, dtype: int, causal: bool) -> int:
     return int(lib.attn_tile_keys(int(D), int(dtype), int(bool(causal))))
+
+
+def attn_launch_rows(B: int, H: int, S: int, D: int, dtype: int, causal: bool) -> int:
+    return int(lib.attn_launch_rows(int(B), int(H), int(S), int(D), int(dtype), int(bool(causal))))
 
 
 def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale, dtype, stream) -> int:

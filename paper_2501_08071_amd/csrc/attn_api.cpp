@@ -45,6 +45,11 @@ extern "C" int attn_tile_rows(int D, int dtype, int causal) {
     return attn_supported(1, D, dtype, causal) ? ATTN_NW * 32 : 0;
 }
 
+extern "C" int attn_launch_rows(int B, int H, int S, int D, int dtype, int causal) {
+    if (B <= 0 || H <= 0 || !attn_supported(S, D, dtype, causal)) return 0;
+    return 32 * attn_pick_nw((long long)B * H, S);
+}
+
 extern "C" int attn_tile_keys(int D, int dtype, int causal) {
     return attn_supported(1, D, dtype, causal) ? attn_block_keys(D) : 0;
 }

@@ -791,7 +791,8 @@ hipError_t launch(const AttnLaunch& a) {
 // dispatch on (dtype, D, causal); arguments were validated by the caller
 hipError_t attn_launch(const AttnLaunch& a) {
 #define ATTN_CASE(DT, DD, CZ)                                       \
-    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ) return launch<DT, DD, CZ, ATTN_NW>(a);
+    if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ)     \
+        return attn_pick_nw(a.BH, a.S) == ATTN_NW ? launch<DT, DD, CZ, ATTN_NW>(a) : launch<DT, DD, CZ, ATTN_NW / 2>(a);
     ATTN_CASE(0, 32, false)
     ATTN_CASE(0, 32, true)
     ATTN_CASE(1, 32, false)

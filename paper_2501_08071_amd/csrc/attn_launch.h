@@ -39,6 +39,17 @@ constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 ? ATTN_NBUF 
 
 static_assert(ATTN_PP_KEYS == 32 || ATTN_PP_KEYS == 64, "block size of the alternating-phase loop");
 
+// Wavefronts per workgroup for a problem of BH (b,h) pairs and S rows: ATTN_NW (256 query rows per workgroup),
+// or half of that when the larger tiles would leave at least half of the 256 compute units without a
+// workgroup (the smaller workgroups also fit two to a compute unit at D <= 64).
+#ifndef ATTN_SMALL_TILES
+#define ATTN_SMALL_TILES 128
+#endif
+inline int attn_pick_nw(long long BH, int S) {
+    const long long tiles = BH * ((S + 32 * ATTN_NW - 1) / (32 * ATTN_NW));
+    return tiles <= ATTN_SMALL_TILES ? ATTN_NW / 2 : ATTN_NW;
+}
+
 struct AttnLaunch {
     const void* q;
     const void* k;

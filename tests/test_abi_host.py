@@ -117,6 +117,10 @@ def test_supported_matrix(P):
                 assert P.attn_supported(1, D, dt, causal) and P.attn_supported(16384, D, dt, causal)
                 assert P.attn_kernel_name(128, D, dt, causal)
                 assert P.attn_tile_rows(D, dt, causal) % 32 == 0 and P.attn_tile_keys(D, dt, causal) > 0
+                assert P.attn_launch_rows(1, 1, 128, D, dt, causal) == 128 and P.attn_launch_rows(8, 64, 4096, D, dt, causal) == 256
+                assert P.attn_launch_rows(1, 128, 256, D, dt, causal) == 128 and P.attn_launch_rows(1, 129, 256, D, dt, causal) == 256
+                assert P.attn_launch_rows(0, 1, 128, D, dt, causal) == 0
+    assert P.attn_launch_rows(1, 1, 128, 96, 0, False) == 0
     assert not P.attn_supported(128, 16, 0, False) and not P.attn_supported(128, 256, 0, False)
     assert not P.attn_supported(128, 64, 2, False)
     assert not P.attn_supported(0, 64, 0, False)

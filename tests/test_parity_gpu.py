@@ -33,6 +33,28 @@ def test_small_shapes_full_compare(B, H, S, D, dtype, causal):
     check_full(q, k, v, dtype, causal, 1 / math.sqrt(D), f"B{B} H{H} S{S} D{D} dt{dtype} causal{causal}")
 
 
+# The same edge lengths with so many (b,h) pairs that the library takes its full-size workgroups (256 query rows,
+# eight wavefronts): with few tiles it launches the same kernel with four wavefronts per workgroup.
+WIDE = [(3, 43, 1, 64), (3, 43, 33, 128), (3, 43, 65, 32), (3, 43, 129, 64), (3, 43, 200, 128), (3, 43, 257, 64),
+        (3, 43, 300, 128), (3, 43, 257, 32)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("B,H,S,D", WIDE)
+def test_small_shapes_full_size_workgroups(B, H, S, D, dtype, causal):
+    assert P.attn_launch_rows(B, H, S, D, dtype, causal) == P.attn_tile_rows(D, dtype, causal) == 256
+    q, k, v = I.gen_tensors(B, H, S, D, dtype, workload_id=500 + S)
+    check_full(q, k, v, dtype, causal, 1 / math.sqrt(D), f"B{B} H{H} S{S} D{D} dt{dtype} causal{causal}")
+
+
+def test_small_problems_take_half_size_workgroups():
+    for (B, H, S, D) in SMALL:
+        assert P.attn_launch_rows(B, H, S, D, F16, False) == 128
+    assert P.attn_launch_rows(1, 4, 4096, 32, F16, True) == 128          # the paper's own shape: 64 large tiles
+    assert P.attn_launch_rows(2, 32, 4096, 128, BF16, True) == 256 and P.attn_launch_rows(4, 16, 1024, 64, F16, False) == 256
+
+
 def test_workload_1_full():
     w = I.workload(1)
     q, k, v = I.gen_inputs(w)
