@@ -21,6 +21,10 @@
 
 #include "gemm_launch.h"
 
+#ifndef GEMM_NST
+#define GEMM_NST 4   // LDS stages of 32 in K; GEMM_NST - 1 of them in flight ahead of the one in use
+#endif
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -94,7 +98,7 @@ __global__ __launch_bounds__(256) void gemm_lrelu_kernel(const uint16_t* __restr
                                                         uint16_t* __restrict__ C, int M, int N, int K, int tiles_m,
                                                         int tiles_n, float slope) {
     using E = Elem<DT>;
-    constexpr int BM = 64 * TM, BN = 64 * TN, NST = 4;
+    constexpr int BM = 64 * TM, BN = 64 * TN, NST = GEMM_NST;
     constexpr int A_TILE = BM * 64;          // BM rows of 32 elements
     constexpr int B_ROWB = 2 * BN;           // bytes per row of the b tile
     constexpr int B_TILE = 32 * B_ROWB;      // 32 rows (k) of BN elements
@@ -255,7 +259,7 @@ __global__ __launch_bounds__(256) void gemm_lrelu_plain_kernel(const uint16_t* _
 template <int DT, int TM, int TN>
 hipError_t launch_tiles(const GemmLaunch& g) {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    constexpr unsigned lds_bytes = 4u * (BM * 64 + 32 * 2 * BN);
+    constexpr unsigned lds_bytes = (unsigned)GEMM_NST * (BM * 64 + 32 * 2 * BN);
     int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const long long blocks = (long long)tiles_m * tiles_n * g.batch;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
