@@ -230,6 +230,7 @@ def main():
                     help="1..5; 3 is the headline (S=4096, D=128, causal, bf16); 6, 7: the paper's own attention shape")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--cold", action="store_true", help="also time with caches flushed between launches")
+    ap.add_argument("--no-probe", action="store_true", help="skip the matrix-instruction-only probe (roofline.mfma_only_measured)")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--data", choices=["synthetic", "zeros"], default="synthetic",
                     help="zeros: all-zero q, k, v -- a diagnostic (same instruction stream, far less switching "
@@ -313,6 +314,14 @@ def main():
                      "algorithmic_bytes": (3 * 2 + 4) * w.B * w.H * w.S * w.D + 4 * w.B * w.H * w.S,
                      "kernel_ms": kern_ms},
     }
+
+    # second denominator: what nothing but matrix instructions of this type sustain on this chip, on random and
+    # on constant operands (the clock under matrix load depends on the operand bits that switch)
+    if not args.no_probe:
+        rnd = P.attn_mfma_probe(dtype=w.dtype, random_operands=True)
+        const = P.attn_mfma_probe(dtype=w.dtype, random_operands=False)
+        out["roofline"]["mfma_only_measured"] = {"random_operands": rnd, "constant_operands": const, "unit": "TFLOP/s",
+                                                  "frac_of_random": achieved / rnd}
 
     if args.cold:
         flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB > L2 + Infinity Cache

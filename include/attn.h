@@ -102,6 +102,17 @@ int attn_tile_keys(int D, int dtype, int causal);
  */
 int attn_launch_rows(int B, int H, int S, int D, int dtype, int causal);
 
+/*
+ * A measuring aid, not part of the attention path: launches `workgroups` workgroups of four wavefronts
+ * that issue nothing but independent 32x32x16 matrix instructions of `dtype`, `iters` x 16 each, on
+ * constant (random_operands == 0) or random operands, and returns the number of floating-point
+ * operations of the launch (-1 on a bad argument or a refused launch).  Timed by the caller, it gives
+ * the rate the matrix cores sustain under load: the second denominator, next to the published peak, that
+ * the throughput of attn_fwd is reported against (the clock under matrix load depends on how many
+ * operand bits switch).  out: DEVICE pointer to workgroups * 256 floats, written.  Asynchronous.
+ */
+long long attn_mfma_probe(float* out, int workgroups, int iters, int dtype, int random_operands, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -48,6 +48,8 @@ def _load() -> ctypes.CDLL:
         f.restype = ctypes.c_int
     lib.attn_launch_rows.argtypes = [ctypes.c_int] * 6
     lib.attn_launch_rows.restype = ctypes.c_int
+    lib.attn_mfma_probe.argtypes = [vp] + [ctypes.c_int] * 4 + [vp]
+    lib.attn_mfma_probe.restype = ctypes.c_longlong
     # include/rowops.h
     lib.softmax_rows_fwd.argtypes = [vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.softmax_rows_fwd.restype = ctypes.c_int
@@ -93,6 +95,25 @@ def attn_tile_keys(D: int, dtype: int, causal: bool) -> int:
 
 def attn_launch_rows(B: int, H: int, S: int, D: int, dtype: int, causal: bool) -> int:
     return int(lib.attn_launch_rows(int(B), int(H), int(S), int(D), int(dtype), int(bool(causal))))
+
+
+def attn_mfma_probe(iters: int = 2000, dtype: int = BF16, random_operands: bool = True, workgroups: int = 2048,
+                    repeats: int = 5) -> float:
+    """TFLOP/s that nothing but matrix instructions sustain (best of `repeats` launches, HIP events)."""
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    st = torch.cuda.current_stream()
+    best = 0.0
+    for i in range(repeats + 1):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        flops = int(lib.attn_mfma_probe(out.data_ptr(), workgroups, iters, int(dtype), int(bool(random_operands)), st.cuda_stream))
+        e1.record(st)
+        torch.cuda.synchronize()
+        if flops < 0:
+            raise RuntimeError("attn_mfma_probe: bad argument or refused launch")
+        if i:      # the first launch warms up
+            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale, dtype, stream) -> int:

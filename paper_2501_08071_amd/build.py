@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
 SOURCES = ["attn_fwd_gfx950.hip", "attn_api.cpp", "rowops_gfx950.hip", "rowops_api.cpp",
-           "gemm_gfx950.hip", "gemm_api.cpp"]
+           "gemm_gfx950.hip", "gemm_api.cpp", "mfma_probe_gfx950.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # packed-fp32 VALU forms are switched off for all device code

@@ -100,6 +100,12 @@ def test_rowops_bad_arguments_rejected_without_a_gpu(P):
     assert rn(0, 0, 0, 0, 64, 1e-6, 0, 0) == 0
 
 
+def test_probe_rejects_bad_arguments(P):
+    f = P.lib.attn_mfma_probe
+    assert f(None, 1, 1, 0, 0, None) == -1 and f(4096, 0, 1, 0, 0, None) == -1 and f(4096, 1, 0, 0, 0, None) == -1
+    assert f(4096, 1, 1, 2, 0, None) == -1 and f(4096, 1 << 20, 1, 0, 0, None) == -1
+
+
 def test_status_strings(P):
     seen = set()
     for st in range(0, -8, -1):

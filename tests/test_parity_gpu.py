@@ -270,3 +270,16 @@ def test_workload_2_every_element():
     q, k, v = I.gen_inputs(w)
     mx, mean, lrel = check_full(q, k, v, w.dtype, w.causal, w.scale, w.name)
     print(f"{w.name} full: max-abs {mx:.2e} mean-abs {mean:.2e} lse-rel {lrel:.2e}")
+
+
+def test_matrix_instruction_probe_runs():
+    """The measuring aid: returns the flop count of its launch and a finite, positive rate; constant operands
+    accumulate exactly (every lane sums iters * 16 instructions * 16 products of 1.0 * 1.0 per accumulator element)."""
+    out = torch.zeros(8 * 256, dtype=torch.float32, device="cuda")
+    flops = P.lib.attn_mfma_probe(out.data_ptr(), 8, 3, BF16, 0, None)
+    torch.cuda.synchronize()
+    assert flops == 8 * 4 * 3 * 16 * 32768
+    assert torch.all(out == 3 * 16 * 16 * 16.0)            # 64 accumulator values per lane, 3 * 4 instructions * 16 products each
+    for dt in (F16, BF16):
+        r = P.attn_mfma_probe(iters=200, dtype=dt, random_operands=True, workgroups=512, repeats=2)
+        assert math.isfinite(r) and r > 0
