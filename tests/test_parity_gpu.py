@@ -265,8 +265,11 @@ def test_workloads_full_size_row_subset(wid):
         assert np.abs(o[:, :, 0] - V[:, :, 0]).max() < 1e-6
 
 
-def test_workload_2_every_element():
-    w = I.workload(2)
+@pytest.mark.parametrize("wid", [2, 3, 5, 4])
+def test_workloads_every_element(wid):
+    """The whole output of every benchmark workload against the oracle (a few seconds of the host's cores for
+    workloads 2, 3 and 5, about half a minute for workload 4)."""
+    w = I.workload(wid)
     q, k, v = I.gen_inputs(w)
     mx, mean, lrel = check_full(q, k, v, w.dtype, w.causal, w.scale, w.name)
     print(f"{w.name} full: max-abs {mx:.2e} mean-abs {mean:.2e} lse-rel {lrel:.2e}")
