@@ -51,8 +51,9 @@ typedef enum {
 int gemm_leakyrelu_fwd(const void* a, const void* b, void* c, int batch, int M, int N, int K, float slope,
                        int dtype, void* stream);
 
-/* Which code path serves this shape: 1 = matrix cores, 128 x 128 tiles; 2 = matrix cores, 64 x 64 tiles;
- * 3 = the plain kernel; 0 = the shape or dtype is not accepted. */
+/* Which code path serves this shape: 1, 2, 3 = matrix cores with tiles of 256 x 256, 128 x 128, 64 x 64 (the
+ * largest that still gives most of the chip a workgroup); 4 = the plain kernel; 0 = the shape or dtype is
+ * not accepted. */
 int gemm_path(int batch, int M, int N, int K, int dtype);
 
 /* Static, NUL-terminated description of a status code; never NULL. */

@@ -85,7 +85,7 @@ __device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcn
 __device__ __forceinline__ constexpr int swz_a(int row) { return (row >> 2) & 3; }
 template <int CHUNKS>
 __device__ __forceinline__ constexpr int swz_b(int row) {
-    return CHUNKS == 16 ? (((row & 3) << 2) | ((row >> 2) & 3))
+    return CHUNKS >= 16 ? (((row & 3) << 2) | ((row >> 2) & 3))   // the low four chunk bits = 256 bytes = all banks
                         : ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1));
 }
 
@@ -93,26 +93,29 @@ __device__ __forceinline__ float leaky(float t, float slope) { return t >= 0.f ?
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
-template <int DT, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_lrelu_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+template <int DT, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_lrelu_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
                                                         uint16_t* __restrict__ C, int M, int N, int K, int tiles_m,
                                                         int tiles_n, float slope) {
     using E = Elem<DT>;
-    constexpr int BM = 64 * TM, BN = 64 * TN, NST = GEMM_NST;
+    constexpr int NW = WM * WN;               // wavefronts, WM x WN over the tile
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN, NST = GEMM_NST;
     constexpr int A_TILE = BM * 64;          // BM rows of 32 elements
     constexpr int B_ROWB = 2 * BN;           // bytes per row of the b tile
     constexpr int B_TILE = 32 * B_ROWB;      // 32 rows (k) of BN elements
     constexpr int STAGE = A_TILE + B_TILE;
     constexpr int B_LPR = B_ROWB / 16;       // lanes (16-byte chunks) per row of the b tile
     constexpr int B_RPI = 64 / B_LPR;        // rows per load instruction
-    constexpr int IPS = TM + TN;             // load instructions per stage and wavefront
-    static_assert(A_TILE / 1024 == 4 * TM && B_TILE / 1024 == 4 * TN, "four wavefronts share the loads evenly");
+    constexpr int LA = A_TILE / 1024 / NW, LB = B_TILE / 1024 / NW;   // load instructions per stage and wavefront
+    constexpr int IPS = LA + LB;
+    static_assert(LA * NW * 1024 == A_TILE && LB * NW * 1024 == B_TILE && LA >= 1 && LB >= 1, "the wavefronts share the loads evenly");
+    static_assert(NST * STAGE <= 160 * 1024, "LDS");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, h = lane >> 5;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WM, wn = wave / WM;
 
     const int bx = blockIdx.x;
     const int tn_i = bx % tiles_n;
@@ -127,18 +130,18 @@ __global__ __launch_bounds__(256) void gemm_lrelu_kernel(const uint16_t* __restr
     const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)smem;
 
     // ---- loads: byte offset of this lane's source chunk inside the tile's rows ----
-    uint32_t goff_a[TM], goff_b[TN];
+    uint32_t goff_a[LA], goff_b[LB];
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int r = 16 * (wave * TM + j) + lane / 4, pos = lane % 4;
+    for (int j = 0; j < LA; ++j) {
+        const int r = 16 * (wave * LA + j) + lane / 4, pos = lane % 4;
         const int rr = r < M - 1 - m0 ? r : M - 1 - m0;
         goff_a[j] = (uint32_t)(rr * K + ((pos ^ swz_a(r)) << 3)) * 2u;
     }
     {
         const int nvalid = (N - n0) / 8 < BN / 8 ? (N - n0) / 8 : BN / 8;   // chunks of this tile inside the matrix
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int r = B_RPI * (wave * TN + j) + lane / B_LPR, pos = lane % B_LPR;
+        for (int j = 0; j < LB; ++j) {
+            const int r = B_RPI * (wave * LB + j) + lane / B_LPR, pos = lane % B_LPR;
             int ch = pos ^ swz_b<B_LPR>(r);
             ch = ch < nvalid - 1 ? ch : nvalid - 1;
             goff_b[j] = (uint32_t)(r * N + (ch << 3)) * 2u;
@@ -151,9 +154,9 @@ __global__ __launch_bounds__(256) void gemm_lrelu_kernel(const uint16_t* __restr
         const uint16_t* sa = Ab + (size_t)kc * 32;
         const uint16_t* sb = Bb + (size_t)kc * 32 * N;
 #pragma unroll
-        for (int j = 0; j < TM; ++j) lds_dma16(lds0 + st * STAGE + (wave * TM + j) * 1024, sa, goff_a[j]);
+        for (int j = 0; j < LA; ++j) lds_dma16(lds0 + st * STAGE + (wave * LA + j) * 1024, sa, goff_a[j]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) lds_dma16(lds0 + st * STAGE + A_TILE + (wave * TN + j) * 1024, sb, goff_b[j]);
+        for (int j = 0; j < LB; ++j) lds_dma16(lds0 + st * STAGE + A_TILE + (wave * LB + j) * 1024, sb, goff_b[j]);
     };
 
     // ---- operand addresses (stage 0, k step 0 of the b tile) ----
@@ -189,30 +192,53 @@ __global__ __launch_bounds__(256) void gemm_lrelu_kernel(const uint16_t* __restr
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s, s);
 
+    // The operands of one k step (16 of the 32 of a block) of stage st
+    struct Ops {
+        u32x4 a[TM], b[TN];
+    };
+    auto read_ops = [&](Ops& o, int st_bytes, int ks) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) o.a[tm] = lds_read_b128(a_addr[tm][ks] + st_bytes);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const u32x2 lo = lds_read_tr16(b_addr[0][tn] + st_bytes + ks * 16 * B_ROWB);
+            const u32x2 hi = lds_read_tr16(b_addr[1][tn] + st_bytes + ks * 16 * B_ROWB);
+            o.b[tn] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        }
+    };
+    auto multiply = [&](const Ops& o) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = E::mfma(o.b[tn], o.a[tm], acc[tn][tm]);
+    };
+
+    // Block kb: its first k step runs on operands read during block kb-1 (`ahead`), its second on operands
+    // read under the first, and under the second the first operands of block kb+1 are read: the matrix
+    // pipe never waits for an LDS round trip behind a barrier.  For that, block kb+1 must be complete one
+    // barrier early: every wavefront checks its share of it before the barrier of block kb.
+    Ops ahead;
+    wait_tile_loads<(NST - 2) * IPS>();
+    __syncthreads();
+    read_ops(ahead, 0, 0);
     auto step = [&](int kb, auto phase) {
         constexpr int PH = decltype(phase)::value;
-        // k block kb has landed when at most the loads of the NST-2 later blocks are still out
-        wait_tile_loads<(NST - 2) * IPS>();
+        // blocks up to kb+1 have landed when at most the loads of the NST-3 later blocks are still out
+        wait_tile_loads<(NST - 3) * IPS>();
         asm volatile("s_barrier" ::: "memory");
         // ... for everybody, and everybody is done with block kb-1: its stage takes block kb+NST-1
         issue(kb + NST - 1, (PH + NST - 1) % NST);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            u32x4 aop[TM], bop[TN];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) aop[tm] = lds_read_b128(a_addr[tm][ks] + PH * STAGE);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const u32x2 lo = lds_read_tr16(b_addr[0][tn] + PH * STAGE + ks * 16 * B_ROWB);
-                const u32x2 hi = lds_read_tr16(b_addr[1][tn] + PH * STAGE + ks * 16 * B_ROWB);
-                bop[tn] = u32x4{lo[0], lo[1], hi[0], hi[1]};
-            }
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = E::mfma(bop[tn], aop[tm], acc[tn][tm]);
-        }
+        Ops second;
+        read_ops(second, PH * STAGE, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(ahead);
+        __builtin_amdgcn_sched_barrier(0);
+        read_ops(ahead, ((PH + 1) % NST) * STAGE, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(second);
+        __builtin_amdgcn_sched_barrier(0);
     };
+    static_assert(NST >= 3, "one block in use, one read ahead, at least one in flight");
     for (int k0 = 0; k0 < nk; k0 += NST) {
         [&]<int... PH>(std::integer_sequence<int, PH...>) {
             ((k0 + PH < nk ? step(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
@@ -256,9 +282,9 @@ __global__ __launch_bounds__(256) void gemm_lrelu_plain_kernel(const uint16_t* _
     }
 }
 
-template <int DT, int TM, int TN>
+template <int DT, int WM, int WN, int TM, int TN>
 hipError_t launch_tiles(const GemmLaunch& g) {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
     constexpr unsigned lds_bytes = (unsigned)GEMM_NST * (BM * 64 + 32 * 2 * BN);
     int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const long long blocks = (long long)tiles_m * tiles_n * g.batch;
@@ -269,9 +295,16 @@ hipError_t launch_tiles(const GemmLaunch& g) {
     int M = g.M, N = g.N, K = g.K;
     float slope = g.slope;
     void* args[] = {&a, &b, &c, &M, &N, &K, &tiles_m, &tiles_n, &slope};
-    const void* fn = reinterpret_cast<const void*>(&gemm_lrelu_kernel<DT, TM, TN>);
-    static_assert(lds_bytes <= 65536u, "within the default dynamic LDS limit");
-    return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(256), args, lds_bytes, (hipStream_t)g.stream);
+    const void* fn = reinterpret_cast<const void*>(&gemm_lrelu_kernel<DT, WM, WN, TM, TN>);
+    if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(WM * WN * 64), args, lds_bytes, (hipStream_t)g.stream);
 }
 
 template <int DT>
@@ -292,8 +325,9 @@ hipError_t launch_plain(const GemmLaunch& g) {
 template <int DT>
 hipError_t dispatch(const GemmLaunch& g) {
     switch (gemm_path_of(g.batch, g.M, g.N, g.K)) {
-        case 1: return launch_tiles<DT, 2, 2>(g);
-        case 2: return launch_tiles<DT, 1, 1>(g);
+        case 1: return launch_tiles<DT, 4, 2, 2, 4>(g);   // 256 x 256, eight wavefronts of 64 x 128
+        case 2: return launch_tiles<DT, 2, 2, 2, 2>(g);   // 128 x 128, four wavefronts of 64 x 64
+        case 3: return launch_tiles<DT, 2, 2, 1, 1>(g);   // 64 x 64, four wavefronts of 32 x 32
         default: return launch_plain<DT>(g);
     }
 }

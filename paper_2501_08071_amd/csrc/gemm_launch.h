@@ -12,11 +12,12 @@ struct GemmLaunch {
     void* stream;
 };
 
-// 1: 128 x 128 tiles, 2: 64 x 64 tiles (both on the matrix cores), 3: plain kernel
+// 1: 256 x 256 tiles, 2: 128 x 128, 3: 64 x 64 (all on the matrix cores), 4: plain kernel.  The largest tile
+// that still gives three quarters of the 256 compute units a workgroup.
 inline int gemm_path_of(int batch, int M, int N, int K) {
-    if (K == 0 || K % 32 != 0 || N % 8 != 0 || K > (1 << 22) || N > (1 << 22)) return 3;   // 32-bit offsets inside a tile's rows
-    const long long big = (long long)batch * ((M + 127) / 128) * ((N + 127) / 128);
-    return big >= 192 ? 1 : 2;   // fewer large tiles than three quarters of the compute units: smaller tiles
+    if (K == 0 || K % 32 != 0 || N % 8 != 0 || K > (1 << 22) || N > (1 << 22)) return 4;   // 32-bit offsets inside a tile's rows
+    auto tiles = [&](int t) { return (long long)batch * ((M + t - 1) / t) * ((N + t - 1) / t); };
+    return tiles(256) >= 192 ? 1 : tiles(128) >= 192 ? 2 : 3;
 }
 
 hipError_t gemm_launch(const GemmLaunch& a);

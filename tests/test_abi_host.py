@@ -49,11 +49,12 @@ def test_gemm_paths_status_and_bad_arguments(P):
     seen = {P.gemm_status_str(st) for st in (0, -1, -2, -3, -4, -6, -7)}
     assert len(seen) == 7 and "unknown status" not in seen and P.gemm_status_str(-5) == "unknown status"
     for dt in (0, 1):
-        assert P.gemm_path(1, 512, 512, 2048, dt) == 2           # the paper's shape: 16 large tiles would leave the chip idle
-        assert P.gemm_path(1, 4096, 4096, 4096, dt) == 1 and P.gemm_path(4, 1024, 1024, 64, dt) == 1
-        assert P.gemm_path(1, 64, 64, 48, dt) == 3 and P.gemm_path(1, 64, 12, 64, dt) == 3 and P.gemm_path(1, 8, 8, 0, dt) == 3
-        assert P.gemm_path(1, 8, 8, 1 << 23, dt) == 3
-        assert P.gemm_path(0, 0, 0, 0, dt) == 3                  # valid and empty
+        assert P.gemm_path(1, 512, 512, 2048, dt) == 3           # the paper's shape: larger tiles would leave the chip idle
+        assert P.gemm_path(1, 4096, 4096, 4096, dt) == 1 and P.gemm_path(4, 1024, 1024, 64, dt) == 2
+        assert P.gemm_path(1, 2048, 2048, 2048, dt) == 2 and P.gemm_path(1, 3584, 3584, 32, dt) == 1
+        assert P.gemm_path(1, 64, 64, 48, dt) == 4 and P.gemm_path(1, 64, 12, 64, dt) == 4 and P.gemm_path(1, 8, 8, 0, dt) == 4
+        assert P.gemm_path(1, 8, 8, 1 << 23, dt) == 4
+        assert P.gemm_path(0, 0, 0, 0, dt) == 4                  # valid and empty
         assert P.gemm_path(-1, 8, 8, 8, dt) == 0 and P.gemm_path(1, 1 << 20, 8, 1 << 20, dt) == 0
     assert P.gemm_path(1, 8, 8, 32, 2) == 0
     ok = 4096

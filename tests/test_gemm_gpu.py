@@ -56,25 +56,34 @@ def run(P, batch, M, N, K, dtype, slope=0.01):
     check(host_bits(c), a, b, slope, dtype, f"gemm {batch}x{M}x{N}x{K} path {P.gemm_path(batch, M, N, K, dtype)}")
 
 
-# (batch, M, N, K): 64 x 64 tiles (path 2) with whole and ragged tiles in M and N, one and several k blocks
+# (batch, M, N, K): 64 x 64 tiles (path 3) with whole and ragged tiles in M and N, one and several k blocks
 SMALL_TILES = [(1, 64, 64, 32), (1, 64, 64, 64), (1, 128, 128, 256), (1, 65, 72, 96), (1, 1, 8, 32), (1, 200, 136, 160),
                (3, 70, 64, 128), (1, 33, 8, 2048), (2, 127, 120, 32)]
-# 128 x 128 tiles (path 1): at least 192 of them
+# 128 x 128 tiles (path 2): at least 192 of them, but fewer than 192 tiles of 256 x 256
 BIG_TILES = [(1, 1792, 1792, 64), (1, 2048, 1536, 96), (2, 1300, 1288, 128), (1, 1793, 1800, 32)]
-# the plain kernel (path 3): K not a multiple of 32, N not a multiple of 8, K = 0
+# 256 x 256 tiles (path 1): at least 192 of them; whole and ragged tiles, one and several k blocks, batches
+HUGE_TILES = [(1, 3584, 3584, 64), (1, 3585, 3592, 32), (3, 2100, 2056, 96), (1, 4096, 3072, 160)]
+# the plain kernel (path 4): K not a multiple of 32, N not a multiple of 8, K = 0
 PLAIN = [(1, 5, 7, 3), (2, 33, 9, 31), (1, 64, 64, 40), (1, 16, 12, 64), (1, 3, 8, 0), (1, 1, 1, 1)]
 
 
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])
 @pytest.mark.parametrize("shape", SMALL_TILES)
 def test_small_tiles(P, shape, dtype):
-    assert P.gemm_path(*shape, dtype) == 2
+    assert P.gemm_path(*shape, dtype) == 3
     run(P, *shape, dtype)
 
 
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])
 @pytest.mark.parametrize("shape", BIG_TILES)
 def test_big_tiles(P, shape, dtype):
+    assert P.gemm_path(*shape, dtype) == 2
+    run(P, *shape, dtype)
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("shape", HUGE_TILES)
+def test_huge_tiles(P, shape, dtype):
     assert P.gemm_path(*shape, dtype) == 1
     run(P, *shape, dtype)
 
@@ -82,7 +91,7 @@ def test_big_tiles(P, shape, dtype):
 @pytest.mark.parametrize("dtype", [I.F16, I.BF16])
 @pytest.mark.parametrize("shape", PLAIN)
 def test_plain_kernel(P, shape, dtype):
-    assert P.gemm_path(*shape, dtype) == 3
+    assert P.gemm_path(*shape, dtype) == 4
     run(P, *shape, dtype)
 
 
