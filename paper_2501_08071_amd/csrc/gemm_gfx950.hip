@@ -7,7 +7,8 @@
 //     the chip enough tiles, else 1 (64 x 64);
 //   * computed transposed, c^T = b^T a^T: the first operand is a 32 x 16 piece of b^T, fetched from the
 //     row-major b tile in LDS with transposing reads (ds_read_b64_tr_b16), the second 16 contiguous bytes
-//     of a row of a; a lane then holds four consecutive n of one row m of c and stores 8 bytes;
+//     of a row of a; a lane then holds four consecutive n of one row m of c, and the tile of c goes out
+//     through LDS so that the stores write whole rows of it;
 //   * K runs in steps of 32 through four LDS stages; tiles come straight from global memory into LDS
 //     (global_load_lds_dwordx4, 16 bytes per lane, 1 KiB of consecutive LDS per instruction), three
 //     stages ahead, with the bank-conflict swizzle applied to the global address of each lane;
@@ -92,6 +93,15 @@ __device__ __forceinline__ constexpr int swz_b(int row) {
 __device__ __forceinline__ float leaky(float t, float slope) { return t >= 0.f ? t : slope * t; }
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+
+// dynamic LDS of a kernel instance: the stages of the loop, or (if larger) the padded blocks of c on their way out
+template <int WM, int WN, int TM, int TN>
+struct GemmLds {
+    static constexpr int STAGES = GEMM_NST * (32 * TM * WM * 64 + 32 * 2 * 32 * TN * WN);
+    static constexpr int OUT = WM * WN * (32 * TM) * (64 * TN + 16);
+    static constexpr int BYTES = STAGES > OUT ? STAGES : OUT;
+    static_assert(BYTES <= 160 * 1024, "LDS");
+};
 
 template <int DT, int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_lrelu_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
@@ -246,20 +256,36 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lrelu_kernel(const uint16_t
     }
     wait_tile_loads<0>();   // the repeated loads of the last steps must not outlive the workgroup's LDS
 
-    // ---- epilogue: activation in fp32, round, 8-byte stores ----
+    // ---- epilogue: activation in fp32, round; the tile leaves through LDS ----
+    // A lane holds four consecutive n of one row m: stored from there, an instruction would touch 32 rows with
+    // 16 bytes each.  Every wavefront writes its 32 TM x 32 TN block into a region of its own (the stages are
+    // free once every wavefront is past the loop and its loads have landed), rows padded by 16 bytes against
+    // bank conflicts, and reads it back with 4 TN lanes side by side on a row: a store instruction then writes
+    // whole rows of the block, 64 TN bytes each.
+    __syncthreads();
+    {
+        constexpr int RW = 32 * TM, RB = 64 * TN, RS = RB + 16;
+        static_assert(NW * RW * RS <= GemmLds<WM, WN, TM, TN>::BYTES, "LDS for the way out");
+        uint8_t* reg = smem + wave * (RW * RS);
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int m = m0 + (wm * TM + tm) * 32 + l32;
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int gg = 0; gg < 4; ++gg) {
-                const int n = n0 + (wn * TN + tn) * 32 + 8 * gg + 4 * h;
-                const f32x16& t = acc[tn][tm];
-                const u32x2 v = {E::pack2(leaky(t[4 * gg], slope), leaky(t[4 * gg + 1], slope)),
-                                 E::pack2(leaky(t[4 * gg + 2], slope), leaky(t[4 * gg + 3], slope))};
-                if (m < M && n < N) *(u32x2*)(Cb + (size_t)m * N + n) = v;
-            }
+                for (int gg = 0; gg < 4; ++gg) {
+                    const f32x16& t = acc[tn][tm];
+                    const u32x2 v = {E::pack2(leaky(t[4 * gg], slope), leaky(t[4 * gg + 1], slope)),
+                                     E::pack2(leaky(t[4 * gg + 2], slope), leaky(t[4 * gg + 3], slope))};
+                    *(u32x2*)(reg + (32 * tm + l32) * RS + 64 * tn + 16 * gg + 8 * h) = v;
+                }
+        constexpr int LPR = RB / 16, RPP = 64 / LPR;   // lanes per row, rows per store instruction
+#pragma unroll
+        for (int p = 0; p < RW / RPP; ++p) {
+            const int row = p * RPP + lane / LPR, ch = lane % LPR;
+            const u32x4 v = *(const u32x4*)(reg + row * RS + ch * 16);
+            const int m = m0 + wm * RW + row, n = n0 + wn * (32 * TN) + ch * 8;
+            if (m < M && n < N) *(u32x4*)(Cb + (size_t)m * N + n) = v;
+        }
     }
 }
 
@@ -285,7 +311,7 @@ __global__ __launch_bounds__(256) void gemm_lrelu_plain_kernel(const uint16_t* _
 template <int DT, int WM, int WN, int TM, int TN>
 hipError_t launch_tiles(const GemmLaunch& g) {
     constexpr int BM = 32 * TM * WM, BN = 32 * TN * WN;
-    constexpr unsigned lds_bytes = (unsigned)GEMM_NST * (BM * 64 + 32 * 2 * BN);
+    constexpr unsigned lds_bytes = (unsigned)GemmLds<WM, WN, TM, TN>::BYTES;
     int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     const long long blocks = (long long)tiles_m * tiles_n * g.batch;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
