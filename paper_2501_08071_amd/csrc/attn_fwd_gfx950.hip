@@ -20,14 +20,16 @@
 //   The two wavefronts of a SIMD share one issue port for vector and matrix instructions, and the
 //   vector work of 32 keys (16 fma, 16 exp, 16 add, 8 convert per lane) is of the order of their
 //   matrix work (16 matrix instructions at D = 128, 8 at D = 64).  Two loop structures:
-//   D = 128  two groups of wavefronts run matrix phases M(k): S(k) = K(k).Q^T, O += V(k-1)^T.P(k-1)^T
+//   D >= 64  two groups of wavefronts run matrix phases M(k): S(k) = K(k).Q^T, O += V(k-1)^T.P(k-1)^T
 //            and vector phases V(k): P(k) = exp2(c S(k) - m) half a block apart, a barrier between
 //            phases: on every SIMD one wavefront feeds the matrix pipe while the other has the vector port;
-//            64 keys per block, so that a phase is 32 matrix instructions long;
-//   D = 64   every wavefront interleaves the matrix instructions of S(k+1) and O += V(k-1)^T.P(k-1)^T
+//            64 keys per block, so that a phase is 32 (D = 128) or 16 (D = 64) matrix instructions long;
+//   D = 32   every wavefront interleaves the matrix instructions of S(k+1) and O += V(k-1)^T.P(k-1)^T
 //            with the vector work of P(k); one barrier per two blocks.
 //   The softmax reference m of a row is the maximum of its first block; it is only taken again when a
-//   block's weight sum overflows a threshold (no row maxima on the hot path).
+//   block's weight sum overflows a threshold (no row maxima on the hot path).  After a reference had to
+//   move, the alternating loop takes the row maxima first for the next ATTN_WARY blocks (a peaked
+//   softmax moves its references block after block at first, and would compute every block's weights twice).
 //
 // Register layout (64-wide wavefront, lane l, half h = l/32, l32 = l%32)
 //   Everything is computed transposed so that one lane only ever holds values of ONE query row:
@@ -155,10 +157,10 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int BC = attn_block_keys(D);
     constexpr int NSUB = BC / 32;      // 32-key sub-blocks (one accumulator tile of S each)
     constexpr int NBUF = attn_buffers(D);   // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
-    // Two loop structures (see below): D = 128 alternates matrix and vector phases between two groups
-    // of wavefronts; D = 64, where the vector work outweighs the matrix work, interleaves both in every
-    // wavefront.
-    constexpr bool PP = ATTN_PINGPONG != 0 && D == 128;
+    // Two loop structures (see below): D = 128 and 64 alternate matrix and vector phases between two
+    // groups of wavefronts; D = 32, where the vector work far outweighs the matrix work, interleaves both
+    // in every wavefront.
+    constexpr bool PP = attn_alternating(D);
     constexpr int BEV = ATTN_BARRIER_EVERY;    // interleaved loop: slots per workgroup barrier (1 or 2)
     static_assert((BEV == 1 || BEV == 2) && NBUF % BEV == 0, "barrier period");
     // block k's step issues the load of K(k + KAHEAD) and of V(k + VAHEAD), into buffers nobody reads
@@ -352,6 +354,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         // first operands of the next matrix phase, read before its barrier
         constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
         u32x4 pre[FETCH];
+        int wary = 0;    // blocks still to go whose row maxima are taken before the weights (wavefront-uniform)
         f32x16 s[NSUB];  // S(k): written by M(k), read by V(k)
         u32x4 pf[NT];    // weights of block k-1 (matrix operand layout) for M(k)
 
@@ -438,8 +441,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     }
                 }
             };
-            if (kb != 0) weights(-m_ref);
-            if (kb == 0 || __builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0) {
+            constexpr int WARY = ATTN_WARY;
+            const bool look_first = kb == 0 || (WARY > 0 && wary > 0);
+            if (!look_first) weights(-m_ref);
+            const bool outgrown = !look_first && __builtin_amdgcn_ballot_w64(!(psum <= __builtin_exp2f(ATTN_MAX_SLACK))) != 0;
+            if (look_first || outgrown) {
                 float mx = vmax3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
                 for (int j = 1; j < 7; ++j) mx = vmax3(mx, s[0][2 * j + 1], s[0][2 * j + 2]);
@@ -450,12 +456,18 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     for (int j = 0; j < 8; ++j) mx = vmax3(mx, s[sub][2 * j], s[sub][2 * j + 1]);
                 }
                 const float m = vmax(mx, other_half(mx)) * c;    // c >= 0
-                const float m_new = m > m_ref ? m : m_ref;
-                const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-                l_run *= alpha;
-                rescale_o(alpha);
-                m_ref = m_new;
+                // after an overflow (and in the first block) the reference goes to the true maximum; while only
+                // looking first, it moves where a logit outgrows it by more than the slack
+                const float m_new = (kb == 0 || outgrown) ? (m > m_ref ? m : m_ref) : (m > m_ref + ATTN_MAX_SLACK ? m : m_ref);
+                const bool moved = __builtin_amdgcn_ballot_w64(m_new != m_ref) != 0;
+                if (moved) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+                    l_run *= alpha;
+                    rescale_o(alpha);
+                    m_ref = m_new;
+                }
                 weights(-m_ref);
+                if (WARY > 0) wary = (outgrown || (moved && kb != 0)) ? WARY : wary - (wary > 0);
             }
             l_run += psum;
 #pragma unroll

@@ -13,6 +13,9 @@
 #ifndef ATTN_MAX_SLACK
 #define ATTN_MAX_SLACK 15.0f  // log2 of the largest sum of 16 softmax weights tolerated before the reference maximum is moved
 #endif
+#ifndef ATTN_WARY
+#define ATTN_WARY 16  // alternating-phase loop: after a reference maximum moved, blocks whose row maxima are taken before the weights
+#endif
 #ifndef ATTN_NBUF
 #define ATTN_NBUF 8   // LDS buffers per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
 #endif
@@ -20,7 +23,7 @@
 #define ATTN_BARRIER_EVERY 2  // key blocks per workgroup barrier (1 or 2)
 #endif
 #ifndef ATTN_PINGPONG
-#define ATTN_PINGPONG 1  // D = 128: alternate matrix and vector phases between two groups of wavefronts
+#define ATTN_PINGPONG 1  // D = 128 and 64: alternate matrix and vector phases between two groups of wavefronts
 #endif
 #ifndef ATTN_HEAD_GROUP
 #define ATTN_HEAD_GROUP 4  // (b,h) pairs whose query tiles an XCD works on at the same time (0: no grouping)
@@ -33,9 +36,9 @@
 #endif
 
 // Which loop a head dimension runs, the keys per inner-loop block and the LDS buffers per tensor that go with it.
-constexpr bool attn_alternating(int D) { return ATTN_PINGPONG != 0 && D == 128; }
+constexpr bool attn_alternating(int D) { return ATTN_PINGPONG != 0 && (D == 128 || D == 64); }
 constexpr int attn_block_keys(int D) { return attn_alternating(D) ? ATTN_PP_KEYS : ATTN_BC; }
-constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 ? ATTN_NBUF / 2 : ATTN_NBUF; }
+constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 && D == 128 ? ATTN_NBUF / 2 : ATTN_NBUF; }   // 128 KiB of blocks at D >= 64
 
 static_assert(ATTN_PP_KEYS == 32 || ATTN_PP_KEYS == 64, "block size of the alternating-phase loop");
 

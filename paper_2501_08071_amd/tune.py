@@ -35,11 +35,11 @@ CACHE = os.path.join(HERE, "tune_cache.json")
 
 # knob -> (macro, ordered values).  A move changes one knob to a neighbouring value.
 KNOBS: Dict[str, Tuple[str, Tuple[int, ...]]] = {
-    "pingpong": ("ATTN_PINGPONG", (0, 1)),          # D = 128: alternate matrix / vector phases between wavefront groups
+    "pingpong": ("ATTN_PINGPONG", (0, 1)),          # D >= 64: alternate matrix / vector phases between wavefront groups
     "barrier_every": ("ATTN_BARRIER_EVERY", (1, 2)),  # interleaved loop: key blocks per workgroup barrier
     "fetch": ("ATTN_FETCH", (2, 4, 6)),             # matrix instructions between an LDS operand read and its use
     "nbuf": ("ATTN_NBUF", (4, 8)),                  # LDS buffers per tensor = how far ahead blocks are requested
-    "block": ("ATTN_PP_KEYS", (32, 64)),            # D = 128, alternating phases: keys per block = work between two barriers
+    "block": ("ATTN_PP_KEYS", (32, 64)),            # alternating phases: keys per block = work between two barriers
 }
 State = Tuple[int, ...]                             # one value per knob, in KNOBS order
 START: State = (0, 1, 2, 4, 32)                     # the plainest schedule: everything interleaved, nothing far ahead
