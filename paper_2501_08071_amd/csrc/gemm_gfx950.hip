@@ -12,6 +12,9 @@
 //   * K runs in steps of 32 through four LDS stages; tiles come straight from global memory into LDS
 //     (global_load_lds_dwordx4, 16 bytes per lane, 1 KiB of consecutive LDS per instruction), three
 //     stages ahead, with the bank-conflict swizzle applied to the global address of each lane;
+//   * the 256 x 256 tile has eight wavefronts, two per SIMD, in two groups that alternate between reading a
+//     block's operands from LDS and issuing its matrix instructions, one phase apart: the matrix pipe of a
+//     SIMD is fed by one wavefront while the other waits for the barrier, for LDS and for its loads;
 //   * rows past M repeat the last row and column chunks past N the last chunk (results masked at the
 //     store), so the loop has no edge cases.
 // Plain kernel (any shape): one thread per element of c, fp32 fused multiply-adds in the order of k.
@@ -22,6 +25,9 @@
 
 #include "gemm_launch.h"
 
+#ifndef GEMM_PINGPONG
+#define GEMM_PINGPONG 1   // eight-wavefront tiles: two groups of wavefronts alternate operand reads and matrix instructions
+#endif
 #ifndef GEMM_NST
 #define GEMM_NST 4   // LDS stages of 32 in K; GEMM_NST - 1 of them in flight ahead of the one in use
 #endif
@@ -223,36 +229,79 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lrelu_kernel(const uint16_t
             for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = E::mfma(o.b[tn], o.a[tm], acc[tn][tm]);
     };
 
-    // Block kb: its first k step runs on operands read during block kb-1 (`ahead`), its second on operands
-    // read under the first, and under the second the first operands of block kb+1 are read: the matrix
-    // pipe never waits for an LDS round trip behind a barrier.  For that, block kb+1 must be complete one
-    // barrier early: every wavefront checks its share of it before the barrier of block kb.
-    Ops ahead;
-    wait_tile_loads<(NST - 2) * IPS>();
-    __syncthreads();
-    read_ops(ahead, 0, 0);
-    auto step = [&](int kb, auto phase) {
-        constexpr int PH = decltype(phase)::value;
-        // blocks up to kb+1 have landed when at most the loads of the NST-3 later blocks are still out
-        wait_tile_loads<(NST - 3) * IPS>();
-        asm volatile("s_barrier" ::: "memory");
-        // ... for everybody, and everybody is done with block kb-1: its stage takes block kb+NST-1
-        issue(kb + NST - 1, (PH + NST - 1) % NST);
-        Ops second;
-        read_ops(second, PH * STAGE, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(ahead);
-        __builtin_amdgcn_sched_barrier(0);
-        read_ops(ahead, ((PH + 1) % NST) * STAGE, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(second);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    static_assert(NST >= 3, "one block in use, one read ahead, at least one in flight");
-    for (int k0 = 0; k0 < nk; k0 += NST) {
-        [&]<int... PH>(std::integer_sequence<int, PH...>) {
-            ((k0 + PH < nk ? step(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
-        }(std::make_integer_sequence<int, NST>{});
+    if constexpr (NW == 8 && GEMM_PINGPONG) {
+        // Eight wavefronts, two per SIMD: two groups (0-3 and 4-7; w and w + 4 share a SIMD) run the same
+        // sequence of phases one phase apart, a barrier between phases.  In its read phase L(k) a wavefront
+        // fetches all operands of block k from LDS into registers; in its matrix phase M(k) it issues the
+        // block's matrix instructions and nothing else: on every SIMD one wavefront feeds the matrix pipe while
+        // the other waits for the barrier, for LDS and for its loads.  Slot 2k: first group L(k), second
+        // M(k-1); slot 2k+1: first group M(k), second L(k).  Block k is read in slots 2k and 2k+1 and those
+        // reads are used up in slots 2k+1 and 2k+2: its stage takes block k + NST in slot 2k+3, from the first
+        // group in its M(k+1) and from the second in its L(k+1).  Every wavefront has its share of block k in
+        // LDS before the barrier that opens slot 2k: all but the loads of the NST-2 later blocks.
+        const bool grp1 = wave >= NW / 2;
+        Ops ops[2];
+        wait_tile_loads<(NST - 2) * IPS>();
+        __syncthreads();
+        if (grp1) asm volatile("s_barrier" ::: "memory");
+        auto step = [&](int kb, auto phase) {
+            constexpr int PH = decltype(phase)::value;
+            wait_tile_loads<(NST - 2) * IPS>();
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(ops[0], PH * STAGE, 0);
+            read_ops(ops[1], PH * STAGE, 1);
+            if (grp1) issue(kb + NST - 1, (PH + NST - 1) % NST);
+            __builtin_amdgcn_sched_barrier(0);
+            wait_tile_loads<(NST - 2) * IPS>();
+            asm volatile("s_barrier" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(ops[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!grp1) issue(kb + NST - 1, (PH + NST - 1) % NST);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(ops[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        static_assert(NST >= 3, "one block in use, at least two in flight");
+        for (int k0 = 0; k0 < nk; k0 += NST) {
+            [&]<int... PH>(std::integer_sequence<int, PH...>) {
+                ((k0 + PH < nk ? step(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
+            }(std::make_integer_sequence<int, NST>{});
+        }
+        if (!grp1) asm volatile("s_barrier" ::: "memory");   // the first group's last one
+    } else {
+        // Block kb: its first k step runs on operands read during block kb-1 (`ahead`), its second on operands
+        // read under the first, and under the second the first operands of block kb+1 are read: the matrix
+        // pipe never waits for an LDS round trip behind a barrier.  For that, block kb+1 must be complete one
+        // barrier early: every wavefront checks its share of it before the barrier of block kb.
+        Ops ahead;
+        wait_tile_loads<(NST - 2) * IPS>();
+        __syncthreads();
+        read_ops(ahead, 0, 0);
+        auto step = [&](int kb, auto phase) {
+            constexpr int PH = decltype(phase)::value;
+            // blocks up to kb+1 have landed when at most the loads of the NST-3 later blocks are still out
+            wait_tile_loads<(NST - 3) * IPS>();
+            asm volatile("s_barrier" ::: "memory");
+            // ... for everybody, and everybody is done with block kb-1: its stage takes block kb+NST-1
+            issue(kb + NST - 1, (PH + NST - 1) % NST);
+            Ops second;
+            read_ops(second, PH * STAGE, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(ahead);
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(ahead, ((PH + 1) % NST) * STAGE, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(second);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        static_assert(NST >= 3, "one block in use, one read ahead, at least one in flight");
+        for (int k0 = 0; k0 < nk; k0 += NST) {
+            [&]<int... PH>(std::integer_sequence<int, PH...>) {
+                ((k0 + PH < nk ? step(k0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
+            }(std::make_integer_sequence<int, NST>{});
+        }
     }
     wait_tile_loads<0>();   // the repeated loads of the last steps must not outlive the workgroup's LDS
 
