@@ -25,10 +25,10 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f16": 2500.0}   # MI355X published dense matrix 
 # only for the kernel source they were taken with (sha256 over the kernel and its configuration header),
 # otherwise reported as null.
 TRAFFIC = {
-    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 149518 * 2.0, "write_kib": 132096 * 1.0,
-                                      "kernel_sha256": "010a6d135e8ceba5043579c319d8686c86b93805da4f64e6a0263540057b1a50"},
-    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 861225 * 2.0, "write_kib": 264192 * 1.0,
-                                       "kernel_sha256": "010a6d135e8ceba5043579c319d8686c86b93805da4f64e6a0263540057b1a50"},
+    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 155902 * 2.0, "write_kib": 132096 * 1.0,
+                                      "kernel_sha256": "8588ab871894aae9d781d31635330ff34a3e98d3cf0dd654f8c91f84a62fc9f3"},
+    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 889285 * 2.0, "write_kib": 264192 * 1.0,
+                                       "kernel_sha256": "8588ab871894aae9d781d31635330ff34a3e98d3cf0dd654f8c91f84a62fc9f3"},
 }
 
 

@@ -17,7 +17,7 @@
 #define ATTN_WARY 16  // alternating-phase loop: after a reference maximum moved, blocks whose row maxima are taken before the weights
 #endif
 #ifndef ATTN_NBUF
-#define ATTN_NBUF 8   // LDS buffers per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
+#define ATTN_NBUF 8   // LDS buffers of 32 keys per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
 #endif
 #ifndef ATTN_BARRIER_EVERY
 #define ATTN_BARRIER_EVERY 2  // key blocks per workgroup barrier (1 or 2)
@@ -38,7 +38,7 @@
 // Which loop a head dimension runs, the keys per inner-loop block and the LDS buffers per tensor that go with it.
 constexpr bool attn_alternating(int D) { return ATTN_PINGPONG != 0 && (D == 128 || D == 64); }
 constexpr int attn_block_keys(int D) { return attn_alternating(D) ? ATTN_PP_KEYS : ATTN_BC; }
-constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 && D == 128 ? ATTN_NBUF / 2 : ATTN_NBUF; }   // 128 KiB of blocks at D >= 64
+constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 ? ATTN_NBUF / 2 : ATTN_NBUF; }   // blocks of 64 keys: half as many (128 KiB at D = 128, 64 KiB at D = 64)
 
 static_assert(ATTN_PP_KEYS == 32 || ATTN_PP_KEYS == 64, "block size of the alternating-phase loop");
 
