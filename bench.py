@@ -41,6 +41,15 @@ ROW_TRAFFIC = {
 }
 
 
+# and for the GEMM + LeakyReLU kernel (the 256 x 256 tile's launches)
+GEMM_TRAFFIC = {
+    "mmLeakyReLu_1x4096x4096x4096_f16": {"fetch_kib": 147536.0 * 2.0, "write_kib": 32768.0 * 1.0,
+                                         "kernel_sha256": "161ba6e0abf2e7cfc2eff4d7fa26857697c82ff2c99a48a4543c819ec5ec0557"},
+    "mmLeakyReLu_1x8192x8192x8192_f16": {"fetch_kib": 786595.4 * 2.0, "write_kib": 131072.0 * 1.0,
+                                         "kernel_sha256": "161ba6e0abf2e7cfc2eff4d7fa26857697c82ff2c99a48a4543c819ec5ec0557"},
+}
+
+
 def kernel_source_sha256(csrc, files=("attn_fwd_gfx950.hip", "attn_launch.h")):
     import hashlib
     h = hashlib.sha256()
@@ -55,6 +64,9 @@ def measured_traffic(workload_name):
     if t is None:
         t = ROW_TRAFFIC.get(workload_name)
         files = ("rowops_gfx950.hip", "rowops_launch.h")
+    if t is None:
+        t = GEMM_TRAFFIC.get(workload_name)
+        files = ("gemm_gfx950.hip", "gemm_launch.h")
     if t is None:
         return None
     csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2501_08071_amd", "csrc")
@@ -200,7 +212,7 @@ def bench_gemm(args):
         "config": {"workload": name, "batch": batch, "M": M, "N": N, "K": K, "slope": 0.01,
                    "path": P.gemm_path(batch, M, N, K, dt)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_TFLOPS["f16"], "traffic": None, "traffic_unit": "bytes/launch",
+                     "frac": achieved / PEAK_TFLOPS["f16"], "traffic": measured_traffic(name), "traffic_unit": "bytes/launch",
                      "algorithmic_bytes": 2 * batch * (M * K + K * N + M * N), "kernel_ms": kern_ms},
     }
     if not args.no_cpu:
