@@ -52,8 +52,9 @@ int gemm_leakyrelu_fwd(const void* a, const void* b, void* c, int batch, int M, 
                        int dtype, void* stream);
 
 /* Which code path serves this shape: 1, 2, 3 = matrix cores with tiles of 256 x 256, 128 x 128, 64 x 64 (the
- * largest that still gives most of the chip a workgroup); 4 = the plain kernel; 0 = the shape or dtype is
- * not accepted. */
+ * largest that still gives most of the chip a workgroup); 5 = matrix cores with tiles of 32 x 32 and K split over
+ * the wavefronts of a workgroup (small problems with K >= 256, the paper's 512 x 512 x 2048 among them); 4 = the
+ * plain kernel; 0 = the shape or dtype is not accepted. */
 int gemm_path(int batch, int M, int N, int K, int dtype);
 
 /* Static, NUL-terminated description of a status code; never NULL. */

@@ -17,6 +17,8 @@
 //     SIMD is fed by one wavefront while the other waits for the barrier, for LDS and for its loads;
 //   * rows past M repeat the last row and column chunks past N the last chunk (results masked at the
 //     store), so the loop has no edge cases.
+// Small problems (at most 256 tiles of 32 x 32, K >= 256): 32 x 32 tiles with K split over the four wavefronts of
+// the workgroup, see gemm_lrelu_splitk_kernel.
 // Plain kernel (any shape): one thread per element of c, fp32 fused multiply-adds in the order of k.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -41,6 +43,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
@@ -338,6 +341,139 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_lrelu_kernel(const uint16_t
     }
 }
 
+
+// Small problems: 32 x 32 tiles of c, K split over the four wavefronts of the workgroup.
+// A problem of few 64 x 64 tiles leaves most compute units without work, and every workgroup pulls its whole
+// strip of a and b through one compute unit's memory pipeline: that, not arithmetic, is what such a launch waits
+// for.  Here a workgroup owns a 32 x 32 tile (four times the workgroups, half the bytes per compute unit) and
+// wavefront w the k blocks w, w + 4, w + 8, ...: it streams them through LDS stages of its own (no barrier in
+// the loop: what a wavefront loads only that wavefront reads), accumulates a 32 x 32 partial result in two
+// independent accumulators, and at the end the four partial results meet in LDS: wavefront q adds up, activates
+// and stores columns 8q .. 8q+7 of the tile.
+#ifndef GEMM_SK_NST
+#define GEMM_SK_NST 4   // LDS stages per wavefront (4 KiB each); more gained nothing and a larger LDS request starts later
+#endif
+template <int DT>
+__global__ __launch_bounds__(256) void gemm_lrelu_splitk_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
+                                                               uint16_t* __restrict__ C, int M, int N, int K, int tiles_m,
+                                                               int tiles_n, float slope) {
+    using E = Elem<DT>;
+    constexpr int NST = GEMM_SK_NST, STAGE = 4096, IPS = 4;
+    static_assert(NST >= 3 && 4 * NST * STAGE <= 160 * 1024 && (NST - 2) * IPS <= 63, "stages");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, h = lane >> 5;
+    const int bx = blockIdx.x;
+    const int tn_i = bx % tiles_n;
+    const int tm_i = (bx / tiles_n) % tiles_m;
+    const int bi = bx / (tiles_n * tiles_m);
+    const int m0 = tm_i * 32, n0 = tn_i * 32;
+    const uint16_t* Ab = A + ((size_t)bi * M + m0) * K;
+    const uint16_t* Bb = B + (size_t)bi * K * N + n0;
+    uint16_t* Cb = C + (size_t)bi * M * N;
+    const int nk = K / 32;
+    const int mine = nk > wave ? (nk - wave + 3) / 4 : 0;   // k blocks of this wavefront: wave, wave + 4, ...
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(LDS_AS uint8_t*)smem;
+    const uint32_t ldsw = lds0 + wave * (NST * STAGE);
+    // loads: instruction j covers rows 16 j .. 16 j + 15 of a tile (64 bytes each); lane = row * 4 + chunk position
+    uint32_t goff_a[2], goff_b[2];
+    {
+        const int nvalid = (N - n0) / 8 < 4 ? (N - n0) / 8 : 4;   // 16-byte chunks of this tile inside the matrix
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int r = 16 * j + lane / 4, pos = lane % 4;
+            const int rr = r < M - 1 - m0 ? r : M - 1 - m0;
+            goff_a[j] = (uint32_t)(rr * K + ((pos ^ swz_a(r)) << 3)) * 2u;
+            int ch = pos ^ swz_a(r);
+            ch = ch < nvalid - 1 ? ch : nvalid - 1;
+            goff_b[j] = (uint32_t)(r * N + (ch << 3)) * 2u;
+        }
+    }
+    // the i-th block of this wavefront into stage st; past its last block the last one again (nobody reads it):
+    // every step issues the same number of loads.  A wavefront without blocks issues nothing.
+    auto issue = [&](int i, int st) {
+        if (mine == 0) return;
+        const int kb = wave + 4 * (i < mine - 1 ? i : mine - 1);
+        const uint16_t* sa = Ab + (size_t)kb * 32;
+        const uint16_t* sb = Bb + (size_t)kb * 32 * N;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) lds_dma16(ldsw + st * STAGE + j * 1024, sa, goff_a[j]);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) lds_dma16(ldsw + st * STAGE + 2048 + j * 1024, sb, goff_b[j]);
+    };
+    // operands (stage 0): a: row l32, chunk 2 ks + h; b^T: 8 bytes of row (k) 8 h + 4 hi + x, elements 16 g1 + 4 y .. +3
+    uint32_t a_addr[2], b_addr[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) a_addr[ks] = ldsw + l32 * 64 + (((2 * ks + h) ^ swz_a(l32)) << 4);
+    {
+        const int x = (lane & 15) >> 2, y = lane & 3, g1 = (lane >> 4) & 1;
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi) {
+            const int row = 8 * h + 4 * hi + x, chunk = 2 * g1 + (y >> 1);
+            b_addr[hi] = ldsw + 2048 + row * 64 + ((chunk ^ swz_a(row)) << 4) + ((y & 1) << 3);
+        }
+    }
+    f32x16 acc[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ks][r] = 0.f;
+
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s, s);
+    auto step = [&](int i, auto phase) {
+        constexpr int PH = decltype(phase)::value;
+        // block i has landed when at most the loads of the NST-2 later blocks are still out
+        wait_tile_loads<(NST - 2) * IPS>();
+        u32x4 a[2], b[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            a[ks] = lds_read_b128(a_addr[ks] + PH * STAGE);
+            const u32x2 lo = lds_read_tr16(b_addr[0] + PH * STAGE + ks * 16 * 64);
+            const u32x2 hi = lds_read_tr16(b_addr[1] + PH * STAGE + ks * 16 * 64);
+            b[ks] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) acc[ks] = E::mfma(b[ks], a[ks], acc[ks]);
+        // the operands are in registers: the stage takes this wavefront's block i + NST - 1
+        issue(i + NST - 1, (PH + NST - 1) % NST);
+    };
+    for (int i0 = 0; i0 < mine; i0 += NST) {
+        [&]<int... PH>(std::integer_sequence<int, PH...>) {
+            ((i0 + PH < mine ? step(i0 + PH, std::integral_constant<int, PH>{}) : (void)0), ...);
+        }(std::make_integer_sequence<int, NST>{});
+    }
+    wait_tile_loads<0>();   // the repeated loads of the last steps must have landed before LDS is used again
+    __syncthreads();
+    // the partial results meet: [wavefront][group of four registers][lane] as 16 bytes each
+    {
+        float* part = (float*)smem;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            f32x4 t;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = acc[0][4 * g + e] + acc[1][4 * g + e];
+            *(f32x4*)(part + ((wave * 4 + g) * 64 + lane) * 4) = t;
+        }
+        __syncthreads();
+        f32x4 t = *(const f32x4*)(part + ((0 * 4 + wave) * 64 + lane) * 4);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const f32x4 u = *(const f32x4*)(part + ((w * 4 + wave) * 64 + lane) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] += u[e];
+        }
+        // registers 4 q .. 4 q + 3 of lane (l32, h) are c[m0 + l32][n0 + 8 q + 4 h .. + 3]
+        const int m = m0 + l32, n = n0 + 8 * wave + 4 * h;
+        if (m < M && n < N) {
+            const u32x2 v = {E::pack2(leaky(t[0], slope), leaky(t[1], slope)), E::pack2(leaky(t[2], slope), leaky(t[3], slope))};
+            *(u32x2*)(Cb + (size_t)m * N + n) = v;
+        }
+    }
+}
+
 // any shape: one thread per element of c
 template <int DT>
 __global__ __launch_bounds__(256) void gemm_lrelu_plain_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ B,
@@ -397,12 +533,37 @@ hipError_t launch_plain(const GemmLaunch& g) {
                            (hipStream_t)g.stream);
 }
 
+
+template <int DT>
+hipError_t launch_splitk(const GemmLaunch& g) {
+    int tiles_m = (g.M + 31) / 32, tiles_n = (g.N + 31) / 32;
+    const long long blocks = (long long)tiles_m * tiles_n * g.batch;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const uint16_t* a = (const uint16_t*)g.a;
+    const uint16_t* b = (const uint16_t*)g.b;
+    uint16_t* c = (uint16_t*)g.c;
+    int M = g.M, N = g.N, K = g.K;
+    float slope = g.slope;
+    void* args[] = {&a, &b, &c, &M, &N, &K, &tiles_m, &tiles_n, &slope};
+    constexpr unsigned lds_bytes = 4u * GEMM_SK_NST * 4096u;
+    const void* fn = reinterpret_cast<const void*>(&gemm_lrelu_splitk_kernel<DT>);
+    if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
+        static bool raised = false;
+        if (!raised) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(256), args, lds_bytes, (hipStream_t)g.stream);
+}
 template <int DT>
 hipError_t dispatch(const GemmLaunch& g) {
     switch (gemm_path_of(g.batch, g.M, g.N, g.K)) {
         case 1: return launch_tiles<DT, 4, 2, 2, 4>(g);   // 256 x 256, eight wavefronts of 64 x 128
         case 2: return launch_tiles<DT, 2, 2, 2, 2>(g);   // 128 x 128, four wavefronts of 64 x 64
         case 3: return launch_tiles<DT, 2, 2, 1, 1>(g);   // 64 x 64, four wavefronts of 32 x 32
+        case 5: return launch_splitk<DT>(g);   // 32 x 32, K split over the four wavefronts
         default: return launch_plain<DT>(g);
     }
 }

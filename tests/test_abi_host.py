@@ -49,7 +49,8 @@ def test_gemm_paths_status_and_bad_arguments(P):
     seen = {P.gemm_status_str(st) for st in (0, -1, -2, -3, -4, -6, -7)}
     assert len(seen) == 7 and "unknown status" not in seen and P.gemm_status_str(-5) == "unknown status"
     for dt in (0, 1):
-        assert P.gemm_path(1, 512, 512, 2048, dt) == 3           # the paper's shape: larger tiles would leave the chip idle
+        assert P.gemm_path(1, 512, 512, 2048, dt) == 5           # the paper's shape: 256 tiles of 32 x 32, K split inside the workgroup
+        assert P.gemm_path(1, 512, 512, 128, dt) == 3 and P.gemm_path(1, 1024, 512, 512, dt) == 3   # K too short; too many tiles
         assert P.gemm_path(1, 4096, 4096, 4096, dt) == 1 and P.gemm_path(4, 1024, 1024, 64, dt) == 2
         assert P.gemm_path(1, 2048, 2048, 2048, dt) == 2 and P.gemm_path(1, 3584, 3584, 32, dt) == 1
         assert P.gemm_path(1, 64, 64, 48, dt) == 4 and P.gemm_path(1, 64, 12, 64, dt) == 4 and P.gemm_path(1, 8, 8, 0, dt) == 4

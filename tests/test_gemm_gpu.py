@@ -57,8 +57,12 @@ def run(P, batch, M, N, K, dtype, slope=0.01):
 
 
 # (batch, M, N, K): 64 x 64 tiles (path 3) with whole and ragged tiles in M and N, one and several k blocks
-SMALL_TILES = [(1, 64, 64, 32), (1, 64, 64, 64), (1, 128, 128, 256), (1, 65, 72, 96), (1, 1, 8, 32), (1, 200, 136, 160),
-               (3, 70, 64, 128), (1, 33, 8, 2048), (2, 127, 120, 32)]
+SMALL_TILES = [(1, 64, 64, 32), (1, 64, 64, 64), (1, 128, 128, 224), (1, 65, 72, 96), (1, 1, 8, 32), (1, 200, 136, 160),
+               (3, 70, 64, 128), (1, 576, 520, 256), (2, 127, 120, 32)]
+# 32 x 32 tiles with K split over the four wavefronts (path 5): at most 256 tiles, K >= 256; whole and ragged tiles,
+# numbers of k blocks that leave wavefronts with unequal shares (9, 11) or fewer blocks than stages, batches
+SPLITK_TILES = [(1, 128, 128, 256), (1, 33, 8, 2048), (1, 320, 264, 288), (3, 200, 136, 352), (1, 1, 8, 256),
+                (1, 512, 480, 1024), (2, 97, 72, 4096)]
 # 128 x 128 tiles (path 2): at least 192 of them, but fewer than 192 tiles of 256 x 256
 BIG_TILES = [(1, 1792, 1792, 64), (1, 2048, 1536, 96), (2, 1300, 1288, 128), (1, 1793, 1800, 32)]
 # 256 x 256 tiles (path 1): at least 192 of them; whole and ragged tiles, one and several k blocks, batches
@@ -71,6 +75,13 @@ PLAIN = [(1, 5, 7, 3), (2, 33, 9, 31), (1, 64, 64, 40), (1, 16, 12, 64), (1, 3, 
 @pytest.mark.parametrize("shape", SMALL_TILES)
 def test_small_tiles(P, shape, dtype):
     assert P.gemm_path(*shape, dtype) == 3
+    run(P, *shape, dtype)
+
+
+@pytest.mark.parametrize("dtype", [I.F16, I.BF16])
+@pytest.mark.parametrize("shape", SPLITK_TILES)
+def test_split_k_tiles(P, shape, dtype):
+    assert P.gemm_path(*shape, dtype) == 5
     run(P, *shape, dtype)
 
 
