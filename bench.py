@@ -41,8 +41,10 @@ ROW_TRAFFIC = {
 }
 
 
-# and for the GEMM + LeakyReLU kernel (the 256 x 256 tile's launches)
+# and for the GEMM + LeakyReLU kernels (the paper's shape; the 256 x 256 tile's launches)
 GEMM_TRAFFIC = {
+    "mmLeakyReLu_1x512x512x2048_f16": {"fetch_kib": 10272.7 * 2.0, "write_kib": 512.0 * 1.0,
+                                       "kernel_sha256": "b6afad5d4c268aac16fd22caac707ccbf4ce59cb3d783dfc272c3eabafb2a914"},
     "mmLeakyReLu_1x4096x4096x4096_f16": {"fetch_kib": 147536.0 * 2.0, "write_kib": 32768.0 * 1.0,
                                          "kernel_sha256": "b6afad5d4c268aac16fd22caac707ccbf4ce59cb3d783dfc272c3eabafb2a914"},
     "mmLeakyReLu_1x8192x8192x8192_f16": {"fetch_kib": 786595.4 * 2.0, "write_kib": 131072.0 * 1.0,
