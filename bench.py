@@ -170,6 +170,25 @@ def bench_rowop(args):
     print(json.dumps(out))
 
 
+def blas_threads():
+    """Threads the numpy matmul of the oracle runs on: the thread pool's own count where it can be asked,
+    else the environment's limit, else the processors of this process."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads") for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return int(max(n))
+    except Exception:
+        pass
+    for var in ("OPENBLAS_NUM_THREADS", "OMP_NUM_THREADS"):
+        if os.environ.get(var, "").isdigit():
+            return int(os.environ[var])
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count()
+
+
 def bench_gemm(args):
     """The paper's fused GEMM + LeakyReLU (Table 2: B, M, N, K = 1, 512, 512, 2048, float16), or a square one of
     --gemm-size.  MFMA roofline: 2 M N K flops per launch."""
@@ -223,7 +242,7 @@ def bench_gemm(args):
         t0 = time.perf_counter()
         G.gemm_leakyrelu(ab[:, :m], bb, 0.01, dt)
         dtm = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": 2.0 * batch * m * N * K / dtm / 1e12, "unit": "TFLOP/s", "cores": os.cpu_count(),
+        out["cpu_baseline"] = {"value": 2.0 * batch * m * N * K / dtm / 1e12, "unit": "TFLOP/s", "cores": blas_threads(),
                                "kind": "oracle", "sample": f"the first {m} of {M} rows of a, {dtm:.2f} s, fp64 numpy matmul",
                                "seconds": dtm}
     print(json.dumps(out))
