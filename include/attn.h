@@ -1,11 +1,10 @@
 /*
  * attn.h -- C ABI of the gfx950 fused multi-head attention forward.
  *
- * The operation is the "fused attention (flash-attention)" kernel class that
- * the paper names as its first example of a specialised LLM kernel
- * (Introduction) and evaluates as one of six kernels (Table 2: B, n_head,
- * seq_len, d_head).  The paper gives no formula; the definition is the
- * standard one:
+ * The operation is the attention kernel class that the paper names first
+ * among the specialised LLM kernels (Introduction) and evaluates as one of
+ * six kernels (Table 2: B, n_head, seq_len, d_head).  The paper gives no
+ * formula; the definition is the standard one:
  *
  *     for every batch b, head h, query row i:
  *         J      = {0..S-1}                     causal == 0
@@ -35,12 +34,12 @@ typedef enum {
     ATTN_ERR_DTYPE = -3,       /* dtype is not an attn_dtype_t                       */
     ATTN_ERR_SCALE = -4,       /* scale is NaN or infinite                           */
     ATTN_ERR_UNSUPPORTED = -5, /* valid request with no kernel instance (D)          */
-    ATTN_ERR_ALIGN = -6,       /* a pointer is not 16-byte aligned                   */
-    ATTN_ERR_LAUNCH = -7       /* the HIP runtime refused the launch                 */
+    ATTN_ERR_LAUNCH = -6,      /* the HIP runtime refused the launch                 */
+    ATTN_ERR_ALIGN = -7        /* a pointer is not 16-byte aligned                   */
 } attn_status_t;
 
 /*
- * Fused attention forward (Table 2's flash-attention row; definition above).
+ * Fused attention forward (the attention row of Table 2; definition above).
  *
  *   q, k, v  DEVICE pointers, [B,H,S,D] contiguous with D fastest, elements of
  *            type `dtype` (IEEE binary16 or bfloat16).  Read only.
@@ -50,12 +49,17 @@ typedef enum {
  *   B,H,S,D  batch, heads, sequence length (queries == keys), head dimension.
  *            Any S >= 1; D must be 32, 64 or 128.
  *   causal   0: every key visible; non-zero: key j visible to query i iff j <= i.
+ *            Masked keys enter the second product with weight 0, so q, k and v must be
+ *            finite everywhere: a non-finite row j of v spoils, next to the rows of O
+ *            that see key j, the earlier rows of the same block of 64 keys (0 * Inf).
  *   scale    multiplies q.k before the softmax; any finite value.
  *   dtype    attn_dtype_t of q, k, v.
  *   stream   hipStream_t to enqueue on (NULL = the default stream).
  *
- * Ownership: the caller owns every buffer; the library allocates nothing, keeps
- * no state and never synchronises.  The call is asynchronous: outputs are valid
+ * Ownership: the caller owns every buffer; the library allocates nothing and
+ * never synchronises.  Its only state is one flag per device and kernel
+ * instance: that the runtime has been told the instance's LDS size (set once,
+ * atomically; calls from several host threads are safe).  The call is asynchronous: outputs are valid
  * once `stream` has been synchronised.  o and lse must not alias q, k or v.
  * All pointers must be 16-byte aligned.
  *
@@ -83,10 +87,12 @@ int attn_supported(int S, int D, int dtype, int causal);
 const char *attn_status_str(int status);
 
 /*
- * Name of the kernel attn_fwd would launch for this request (the symbol a
- * profiler reports), or NULL if unsupported.  Static storage, no HIP call.
+ * Name of the kernel attn_fwd launches for this very problem (the symbol a
+ * profiler reports; it depends on B and H because small problems take the
+ * instance with half the wavefronts, see attn_launch_rows), or NULL if
+ * unsupported.  A string constant: no HIP call, safe from any thread.
  */
-const char *attn_kernel_name(int S, int D, int dtype, int causal);
+const char *attn_kernel_name(int B, int H, int S, int D, int dtype, int causal);
 
 /*
  * Query rows per workgroup and keys per inner-loop tile of that kernel
@@ -101,17 +107,6 @@ int attn_tile_keys(int D, int dtype, int causal);
  * that the larger ones would leave half of the chip idle.  0 if unsupported.
  */
 int attn_launch_rows(int B, int H, int S, int D, int dtype, int causal);
-
-/*
- * A measuring aid, not part of the attention path: launches `workgroups` workgroups of four wavefronts
- * that issue nothing but independent 32x32x16 matrix instructions of `dtype`, `iters` x 16 each, on
- * constant (random_operands == 0) or random operands, and returns the number of floating-point
- * operations of the launch (-1 on a bad argument or a refused launch).  Timed by the caller, it gives
- * the rate the matrix cores sustain under load: the second denominator, next to the published peak, that
- * the throughput of attn_fwd is reported against (the clock under matrix load depends on how many
- * operand bits switch).  out: DEVICE pointer to workgroups * 256 floats, written.  Asynchronous.
- */
-long long attn_mfma_probe(float* out, int workgroups, int iters, int dtype, int random_operands, void* stream);
 
 #ifdef __cplusplus
 }

@@ -2,8 +2,8 @@
  * gemm.h -- C ABI of the fused GEMM + LeakyReLU for gfx950.
  *
  * The paper's second compute-bound kernel (Table 2: mmLeakyReLu, B, M, N, K =
- * 1, 512, 512, 2048, float16; Section 5.1: "fused GEMM and epilogue
- * (Leaky-ReLU)"; Section 5.4 analyses its schedule).  No formula is given;
+ * 1, 512, 512, 2048, float16; Section 5.1 describes it as a matrix product with
+ * the activation fused into its epilogue; Section 5.4 analyses its schedule).  No formula is given;
  * the definition is the plain one:
  *
  *     c[i, m, n] = f( sum_k a[i, m, k] * b[i, k, n] ),   f(t) = t if t >= 0 else slope * t

@@ -5,9 +5,8 @@
  * GPU kernel is checked against.  It shares no code, header, table or helper
  * with the HIP path and must never be called from the product path.
  *
- * What it computes (the paper only names the operation -- "fused attention
- * (flash-attention)", Introduction and Table 2 -- so the definition is the
- * textbook one):
+ * What it computes (the paper only names the operation, in its Introduction
+ * and in Table 2, so the definition is the textbook one):
  *
  *   for every batch b, head h and query row i
  *       J      = {0..S-1}            (non-causal)
@@ -74,7 +73,7 @@ double oracle_widen(unsigned int bits16, int dtype) { return widen((uint16_t)bit
  *   rows[nrows]            query-row indices in [0,S)
  *   o   [B*H, nrows, D]    fp64 out
  *   lse [B*H, nrows]       fp64 out, natural log
- * Returns 0, or -1 on a bad argument.
+ * Returns 0, or -1 on a bad argument or when memory runs out (o and lse are then not to be used).
  */
 int attn_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
                      int B, int H, int S, int D, int causal, double scale, int dtype,
@@ -87,14 +86,21 @@ int attn_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
         if (rows[r] < 0 || rows[r] >= S) return -1;
 
     const long BH = (long)B * H;
+    int out_of_memory = 0;   /* set by any thread whose work buffers could not be had */
 #pragma omp parallel
     {
         double *kd = malloc(sizeof(double) * (size_t)S * D);   /* one head of K, widened */
         double *vd = malloc(sizeof(double) * (size_t)S * D);
         double *s  = malloc(sizeof(double) * (size_t)S);
         double *qd = malloc(sizeof(double) * (size_t)D);
+        const int have = kd && vd && s && qd;
+        if (!have) {
+#pragma omp atomic write
+            out_of_memory = 1;
+        }
 #pragma omp for schedule(dynamic, 1)
         for (long bh = 0; bh < BH; ++bh) {
+            if (!have) continue;   /* the call fails as a whole, see below */
             const uint16_t *qh = q + (size_t)bh * S * D;
             const uint16_t *kh = k + (size_t)bh * S * D;
             const uint16_t *vh = v + (size_t)bh * S * D;
@@ -129,7 +135,7 @@ int attn_oracle_rows(const uint16_t *q, const uint16_t *k, const uint16_t *v,
         }
         free(kd); free(vd); free(s); free(qd);
     }
-    return 0;
+    return out_of_memory ? -1 : 0;
 }
 
 /* All rows: o [B,H,S,D], lse [B,H,S]. */

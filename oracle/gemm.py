@@ -1,7 +1,8 @@
 """fp64 CPU oracle for the fused GEMM + LeakyReLU -- TEST INFRASTRUCTURE ONLY.
 
 The paper's second compute-bound kernel (Table 2: mmLeakyReLu, B, M, N, K = 1, 512, 512, 2048, float16;
-Section 5.1: "fused GEMM and epilogue (Leaky-ReLU)"; Section 5.4 studies its schedule).  No formula is
+Section 5.1 describes it as a matrix product with the activation fused into its epilogue; Section 5.4 studies
+its schedule).  No formula is
 given; the plain definition is
 
     c[b, m, n] = f( sum_k a[b, m, k] * b[b, k, n] ),      f(t) = t if t >= 0 else slope * t

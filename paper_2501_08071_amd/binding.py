@@ -41,15 +41,22 @@ def _load() -> ctypes.CDLL:
     lib.attn_supported.restype = ctypes.c_int
     lib.attn_status_str.argtypes = [ctypes.c_int]
     lib.attn_status_str.restype = ctypes.c_char_p
-    lib.attn_kernel_name.argtypes = [ctypes.c_int] * 4
+    lib.attn_kernel_name.argtypes = [ctypes.c_int] * 6
     lib.attn_kernel_name.restype = ctypes.c_char_p
     for f in (lib.attn_tile_rows, lib.attn_tile_keys):
         f.argtypes = [ctypes.c_int] * 3
         f.restype = ctypes.c_int
     lib.attn_launch_rows.argtypes = [ctypes.c_int] * 6
     lib.attn_launch_rows.restype = ctypes.c_int
-    lib.attn_mfma_probe.argtypes = [vp] + [ctypes.c_int] * 4 + [vp]
-    lib.attn_mfma_probe.restype = ctypes.c_longlong
+    # include/probe.h
+    lib.probe_mfma.argtypes = [vp] + [ctypes.c_int] * 4 + [vp]
+    lib.probe_mfma.restype = ctypes.c_longlong
+    lib.probe_softmax_valu.argtypes = [vp] + [ctypes.c_int] * 3 + [vp]
+    lib.probe_softmax_valu.restype = ctypes.c_longlong
+    lib.probe_l2_read.argtypes = [vp, vp] + [ctypes.c_int] * 3 + [vp]
+    lib.probe_l2_read.restype = ctypes.c_longlong
+    lib.probe_empty.argtypes = [ctypes.c_int, ctypes.c_int, vp]
+    lib.probe_empty.restype = ctypes.c_int
     # include/rowops.h
     lib.softmax_rows_fwd.argtypes = [vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.softmax_rows_fwd.restype = ctypes.c_int
@@ -80,8 +87,8 @@ def attn_supported(S: int, D: int, dtype: int, causal: bool) -> bool:
     return bool(lib.attn_supported(int(S), int(D), int(dtype), int(bool(causal))))
 
 
-def attn_kernel_name(S: int, D: int, dtype: int, causal: bool):
-    n = lib.attn_kernel_name(int(S), int(D), int(dtype), int(bool(causal)))
+def attn_kernel_name(B: int, H: int, S: int, D: int, dtype: int, causal: bool):
+    n = lib.attn_kernel_name(int(B), int(H), int(S), int(D), int(dtype), int(bool(causal)))
     return n.decode() if n else None
 
 
@@ -97,23 +104,60 @@ def attn_launch_rows(B: int, H: int, S: int, D: int, dtype: int, causal: bool) -
     return int(lib.attn_launch_rows(int(B), int(H), int(S), int(D), int(dtype), int(bool(causal))))
 
 
-def attn_mfma_probe(iters: int = 2000, dtype: int = BF16, random_operands: bool = True, workgroups: int = 2048,
-                    repeats: int = 5) -> float:
-    """TFLOP/s that nothing but matrix instructions sustain (best of `repeats` launches, HIP events)."""
-    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+# ---- include/probe.h: measuring aids (no product path calls them) -------------------------------
+
+def _timed_probe(launch, repeats: int) -> float:
+    """Best rate (units of the launch's return value per second) of `repeats` launches after one warm-up."""
     st = torch.cuda.current_stream()
     best = 0.0
     for i in range(repeats + 1):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(st)
-        flops = int(lib.attn_mfma_probe(out.data_ptr(), workgroups, iters, int(dtype), int(bool(random_operands)), st.cuda_stream))
+        n = int(launch(st.cuda_stream))
         e1.record(st)
         torch.cuda.synchronize()
-        if flops < 0:
-            raise RuntimeError("attn_mfma_probe: bad argument or refused launch")
-        if i:      # the first launch warms up
-            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        if n < 0:
+            raise RuntimeError("probe: bad argument or refused launch")
+        if i:
+            best = max(best, n / (e0.elapsed_time(e1) * 1e-3))
     return best
+
+
+def probe_mfma(iters: int = 2000, dtype: int = BF16, random_operands: bool = True, workgroups: int = 2048,
+               repeats: int = 5) -> float:
+    """TFLOP/s that nothing but matrix instructions sustain (best of `repeats` launches, HIP events)."""
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    return _timed_probe(lambda st: lib.probe_mfma(out.data_ptr(), workgroups, iters, int(dtype), int(bool(random_operands)), st),
+                        repeats) / 1e12
+
+
+def probe_softmax_valu(iters: int = 4000, full: bool = True, workgroups: int = 2048, repeats: int = 3) -> float:
+    """Scores per second whose softmax vector work (multiply-add, exp2; with `full` also the row-sum addition and the
+    conversion to bfloat16) the vector pipes sustain when they do nothing else."""
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    return _timed_probe(lambda st: lib.probe_softmax_valu(out.data_ptr(), workgroups, iters, int(bool(full)), st), repeats)
+
+
+def probe_l2_read(region_kib: int = 1024, iters: int = 64, workgroups: int = 2048, repeats: int = 3) -> float:
+    """Bytes per second the compute units read from regions that stay in their XCD's L2."""
+    buf = torch.zeros(8 * region_kib * 256, dtype=torch.int32, device="cuda")
+    out = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    return _timed_probe(lambda st: lib.probe_l2_read(buf.data_ptr(), out.data_ptr(), region_kib, workgroups, iters, st), repeats)
+
+
+def probe_launch_floor_us(workgroups: int = 256, threads: int = 256, launches: int = 200) -> float:
+    """Microseconds per launch of a kernel that does nothing, back to back on the current stream (mean)."""
+    st = torch.cuda.current_stream()
+    for _ in range(20):
+        lib.probe_empty(workgroups, threads, st.cuda_stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for _ in range(launches):
+        if lib.probe_empty(workgroups, threads, st.cuda_stream) != 0:
+            raise RuntimeError("probe_empty: bad argument or refused launch")
+    e1.record(st)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / launches
 
 
 def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale, dtype, stream) -> int:

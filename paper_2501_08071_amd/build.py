@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
 SOURCES = ["attn_fwd_gfx950.hip", "attn_api.cpp", "rowops_gfx950.hip", "rowops_api.cpp",
-           "gemm_gfx950.hip", "gemm_api.cpp", "mfma_probe_gfx950.hip"]
+           "gemm_gfx950.hip", "gemm_api.cpp", "probe_gfx950.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # packed-fp32 VALU forms are switched off for all device code
@@ -34,7 +34,7 @@ def lib_is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", h) for h in ("attn.h", "rowops.h", "gemm.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", h) for h in ("attn.h", "rowops.h", "gemm.h", "probe.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

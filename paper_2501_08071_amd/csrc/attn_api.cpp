@@ -32,13 +32,34 @@ extern "C" const char* attn_status_str(int status) {
     }
 }
 
-extern "C" const char* attn_kernel_name(int S, int D, int dtype, int causal) {
-    if (!attn_supported(S, D, dtype, causal)) return nullptr;
-    static char names[2][3][2][64];
-    char* n = names[dtype][D == 32 ? 0 : D == 64 ? 1 : 2][causal != 0];
-    if (n[0] == 0)
-        std::snprintf(n, 64, "attn_fwd_kernel<%d, %d, %s, %d>", dtype, D, causal ? "true" : "false", ATTN_NW);
-    return n;
+// The names a profiler reports, one string constant per instance (nothing is built at run time).
+#define ATTN_STR2(x) #x
+#define ATTN_STR(x) ATTN_STR2(x)
+#define ATTN_NAME(DT, DD, CZ, NWS) "attn_fwd_kernel<" #DT ", " #DD ", " #CZ ", " NWS ">"
+#define ATTN_NAMES_NW(NWS)                                                                              \
+    {{{ATTN_NAME(0, 32, false, NWS), ATTN_NAME(0, 32, true, NWS)},                                      \
+      {ATTN_NAME(0, 64, false, NWS), ATTN_NAME(0, 64, true, NWS)},                                      \
+      {ATTN_NAME(0, 128, false, NWS), ATTN_NAME(0, 128, true, NWS)}},                                   \
+     {{ATTN_NAME(1, 32, false, NWS), ATTN_NAME(1, 32, true, NWS)},                                      \
+      {ATTN_NAME(1, 64, false, NWS), ATTN_NAME(1, 64, true, NWS)},                                      \
+      {ATTN_NAME(1, 128, false, NWS), ATTN_NAME(1, 128, true, NWS)}}}
+#if ATTN_NW == 8
+#define ATTN_NW_FULL_STR "8"
+#define ATTN_NW_HALF_STR "4"
+#elif ATTN_NW == 4
+#define ATTN_NW_FULL_STR "4"
+#define ATTN_NW_HALF_STR "2"
+#else
+#error "attn_kernel_name: add the strings for this ATTN_NW"
+#endif
+namespace {
+const char* const kKernelNames[2][2][3][2] = {ATTN_NAMES_NW(ATTN_NW_FULL_STR), ATTN_NAMES_NW(ATTN_NW_HALF_STR)};
+}  // namespace
+
+extern "C" const char* attn_kernel_name(int B, int H, int S, int D, int dtype, int causal) {
+    if (B <= 0 || H <= 0 || !attn_supported(S, D, dtype, causal)) return nullptr;
+    const int half = attn_pick_nw((long long)B * H, S) == ATTN_NW ? 0 : 1;
+    return kKernelNames[half][dtype][D == 32 ? 0 : D == 64 ? 1 : 2][causal != 0];
 }
 
 extern "C" int attn_tile_rows(int D, int dtype, int causal) {

@@ -46,67 +46,14 @@
 #include <type_traits>
 
 #include "attn_launch.h"
+#include "gfx950_common.h"
 
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+using namespace gfx950;
 
-#define LDS_AS __attribute__((address_space(3)))
-
-template <int DT> struct Elem;
-template <> struct Elem<0> {  // IEEE binary16
-    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // round to nearest even
-        f32x2 x = {lo, hi};
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));
-    }
-    static __device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {  // acc + p.lo + p.hi
-        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, p), f16x2{(_Float16)1.0f, (_Float16)1.0f}, acc, false);
-    }
-};
-template <> struct Elem<1> {  // bfloat16
-    static __device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // round to nearest even
-        f32x2 x = {lo, hi};
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-    }
-    static __device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {  // acc + p.lo + p.hi
-        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p), bf16x2{(__bf16)1.0f, (__bf16)1.0f}, acc, false);
-    }
-};
-
-// 4 x 16-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
-// the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4 of its group.
-__device__ __forceinline__ u32x2 lds_read_tr16(uint32_t addr) {
-    s16x4 t = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(uintptr_t)addr);
-    return __builtin_bit_cast(u32x2, t);
-}
-
-// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds_base + 16 l
-// (lds_base wave-uniform, a multiple of 16).  Written as asm so that the compiler's wait-count
-// insertion does not know about the transfer: it would otherwise wait for ALL outstanding tile
-// loads in front of LDS reads of the other buffer.  The wait is explicit, before the tile barrier.
-__device__ __forceinline__ void lds_dma16(uint32_t lds_base, const void* gbase, uint32_t byte_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_base), "v"(byte_off), "s"(gbase) : "memory", "m0");
-}
-// wait until at most N of this wavefront's direct-to-LDS loads are still in flight (they land in order)
 template <int N>
-__device__ __forceinline__ void wait_block_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
-__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr) { return *(const LDS_AS u32x4*)(uintptr_t)addr; }
+__device__ __forceinline__ void wait_block_loads() { wait_lds_dma<N>(); }
 
 // plain maxima, without the quiet-NaN canonicalisation the C library semantics would add
 __device__ __forceinline__ float vmax(float a, float b) {
@@ -787,14 +734,8 @@ hipError_t launch(const AttnLaunch& a) {
     // NBUF K and NBUF V block buffers, and 4 KB per wavefront for the way out of the output tile
     constexpr unsigned lds_bytes = 2u * attn_buffers(D) * attn_block_keys(D) * 2u * D + NW * 4096u;
     const void* fn = reinterpret_cast<const void*>(&attn_fwd_kernel<DT, D, CAUSAL, NW>);
-    if (lds_bytes > 65536u) {   // above the default limit the runtime wants to be told once per kernel
-        static bool raised = false;
-        if (!raised) {
-            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
-    }
+    static std::atomic<uint64_t> told{0};   // per kernel instance: the devices whose runtime knows its LDS size
+    if (const hipError_t e = announce_lds(fn, lds_bytes, told); e != hipSuccess) return e;
     return hipLaunchKernel(fn, dim3((unsigned)blocks), dim3(NW * 64), args, lds_bytes, (hipStream_t)a.stream);
 }
 

@@ -42,7 +42,13 @@ def test_every_declared_symbol_is_exported(P):
     assert names == ["gemm_leakyrelu_fwd", "gemm_path", "gemm_status_str"]
     for n in names:
         assert hasattr(P.lib, n), f"{n} is declared in gemm.h but not exported"
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["attn.h", "gemm.h", "rowops.h"]
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "probe.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(probe_[a-z0-9_]+)\s*\(", text)))
+    assert names == ["probe_empty", "probe_l2_read", "probe_mfma", "probe_softmax_valu"]
+    for n in names:
+        assert hasattr(P.lib, n), f"{n} is declared in probe.h but not exported"
+    assert not any(n.startswith("probe") or "probe" in n for n in declared_symbols())   # measuring aids stay out of attn.h
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["attn.h", "gemm.h", "probe.h", "rowops.h"]
 
 
 def test_gemm_paths_status_and_bad_arguments(P):
@@ -102,10 +108,18 @@ def test_rowops_bad_arguments_rejected_without_a_gpu(P):
     assert rn(0, 0, 0, 0, 64, 1e-6, 0, 0) == 0
 
 
-def test_probe_rejects_bad_arguments(P):
-    f = P.lib.attn_mfma_probe
+def test_probes_reject_bad_arguments(P):
+    f = P.lib.probe_mfma
     assert f(None, 1, 1, 0, 0, None) == -1 and f(4096, 0, 1, 0, 0, None) == -1 and f(4096, 1, 0, 0, 0, None) == -1
     assert f(4096, 1, 1, 2, 0, None) == -1 and f(4096, 1 << 20, 1, 0, 0, None) == -1
+    g = P.lib.probe_softmax_valu
+    assert g(None, 1, 1, 0, None) == -1 and g(4096, 0, 1, 0, None) == -1 and g(4096, 1, 0, 1, None) == -1
+    h = P.lib.probe_l2_read
+    assert h(None, 4096, 1024, 8, 1, None) == -1 and h(4096, None, 1024, 8, 1, None) == -1
+    assert h(4096, 4096, 1000, 8, 1, None) == -1 and h(4096, 4096, 0, 8, 1, None) == -1      # not whole steps
+    assert h(4096 + 4, 4096, 1024, 8, 1, None) == -1 and h(4096, 4096, 1024, 0, 1, None) == -1
+    e = P.lib.probe_empty
+    assert e(0, 64, None) == -1 and e(1, 0, None) == -1 and e(1, 2048, None) == -1
 
 
 def test_status_strings(P):
@@ -123,7 +137,9 @@ def test_supported_matrix(P):
         for dt in (0, 1):
             for causal in (False, True):
                 assert P.attn_supported(1, D, dt, causal) and P.attn_supported(16384, D, dt, causal)
-                assert P.attn_kernel_name(128, D, dt, causal)
+                small, large = P.attn_kernel_name(1, 1, 128, D, dt, causal), P.attn_kernel_name(8, 64, 4096, D, dt, causal)
+                assert small == f"attn_fwd_kernel<{dt}, {D}, {'true' if causal else 'false'}, 4>"
+                assert large == f"attn_fwd_kernel<{dt}, {D}, {'true' if causal else 'false'}, 8>"
                 assert P.attn_tile_rows(D, dt, causal) % 32 == 0 and P.attn_tile_keys(D, dt, causal) > 0
                 assert P.attn_launch_rows(1, 1, 128, D, dt, causal) == 128 and P.attn_launch_rows(8, 64, 4096, D, dt, causal) == 256
                 assert P.attn_launch_rows(1, 128, 256, D, dt, causal) == 128 and P.attn_launch_rows(1, 129, 256, D, dt, causal) == 256
@@ -132,7 +148,7 @@ def test_supported_matrix(P):
     assert not P.attn_supported(128, 16, 0, False) and not P.attn_supported(128, 256, 0, False)
     assert not P.attn_supported(128, 64, 2, False)
     assert not P.attn_supported(0, 64, 0, False)
-    assert P.attn_kernel_name(128, 96, 0, False) is None
+    assert P.attn_kernel_name(1, 1, 128, 96, 0, False) is None and P.attn_kernel_name(0, 1, 128, 64, 0, False) is None
 
 
 @pytest.mark.parametrize("entry", ["attn_fwd_raw", "attn_fwd_o16_raw"])
@@ -152,7 +168,39 @@ def test_bad_arguments_rejected_without_a_gpu(P, entry):
     assert f(ok, ok, ok, ok, ok, 1, 1, 8, 64, 0, float("nan"), 0, 0) == -4
     assert f(ok, ok, ok, ok, ok, 1, 1, 8, 64, 0, float("inf"), 0, 0) == -4
     assert f(ok, ok, ok, ok, ok, 1, 1, 8, 96, 0, 1.0, 0, 0) == -5
-    assert f(ok + 8, ok, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -6
+    assert f(ok + 8, ok, ok, ok, ok, 1, 1, 8, 64, 0, 1.0, 0, 0) == -7    # -6 is a refused launch, which needs a GPU to happen
+
+
+def test_queries_from_two_threads_agree(P):
+    """The query entry points and the argument checks keep no lazily built state: two host threads that call them at the
+    same time get the answers of a single thread."""
+    import threading
+
+    def answers():
+        out = []
+        for _ in range(200):
+            for D in (32, 64, 128, 96):
+                for dt in (0, 1):
+                    for causal in (0, 1):
+                        out.append((P.attn_kernel_name(1, 3, 500, D, dt, causal), P.attn_kernel_name(4, 64, 500, D, dt, causal),
+                                    P.attn_launch_rows(2, 2, 999, D, dt, causal), P.attn_tile_keys(D, dt, causal),
+                                    P.attn_fwd_raw(4096, 4096, 4096, 4096 + 8, 0, 1, 1, 8, D, causal, 1.0, dt, 0),
+                                    P.attn_fwd_raw(4096, 4096, 0, 4096, 0, 1, 1, 8, D, causal, 1.0, dt, 0),
+                                    P.attn_status_str(-7)))
+        return out
+
+    want = answers()
+    got = [None, None]
+
+    def run(i):
+        got[i] = answers()
+
+    ts = [threading.Thread(target=run, args=(i,)) for i in range(2)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert got[0] == want and got[1] == want
 
 
 def test_library_links_only_the_hip_runtime():

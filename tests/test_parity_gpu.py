@@ -279,10 +279,10 @@ def test_matrix_instruction_probe_runs():
     """The measuring aid: returns the flop count of its launch and a finite, positive rate; constant operands
     accumulate exactly (every lane sums iters * 16 instructions * 16 products of 1.0 * 1.0 per accumulator element)."""
     out = torch.zeros(8 * 256, dtype=torch.float32, device="cuda")
-    flops = P.lib.attn_mfma_probe(out.data_ptr(), 8, 3, BF16, 0, None)
+    flops = P.lib.probe_mfma(out.data_ptr(), 8, 3, BF16, 0, None)
     torch.cuda.synchronize()
     assert flops == 8 * 4 * 3 * 16 * 32768
     assert torch.all(out == 3 * 16 * 16 * 16.0)            # 64 accumulator values per lane, 3 * 4 instructions * 16 products each
     for dt in (F16, BF16):
-        r = P.attn_mfma_probe(iters=200, dtype=dt, random_operands=True, workgroups=512, repeats=2)
+        r = P.probe_mfma(iters=200, dtype=dt, random_operands=True, workgroups=512, repeats=2)
         assert math.isfinite(r) and r > 0
