@@ -37,7 +37,7 @@ CSRC = os.path.join(ROOT, "paper_2501_08071_amd", "csrc")
 # scaled by what the same counter reads for a plain 1 GiB copy: 2.0 and 1.0), keyed by workload, with the
 # summary under profiles/ that holds the counter values; valid only for the kernel source they were taken
 # with (sha256 over the kernel's sources), otherwise reported as null.
-ATTN_FILES = ("attn_fwd_gfx950.hip", "attn_launch.h", "gfx950_common.h")
+ATTN_FILES = ("attn_fwd_gfx950.hip", "attn_fwd_rows64_gfx950.hip", "attn_launch.h", "attn_device.h", "gfx950_common.h")
 ROW_FILES = ("rowops_gfx950.hip", "rowops_launch.h")
 GEMM_FILES = ("gemm_gfx950.hip", "gemm_launch.h", "gfx950_common.h")
 TRAFFIC = {

@@ -2,31 +2,55 @@
 from __future__ import annotations
 
 import os
+import shutil
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libattn_gfx950.so")
-SOURCES = ["attn_fwd_gfx950.hip", "attn_api.cpp", "rowops_gfx950.hip", "rowops_api.cpp",
+SOURCES = ["attn_fwd_gfx950.hip", "attn_fwd_rows64_gfx950.hip", "attn_api.cpp", "rowops_gfx950.hip", "rowops_api.cpp",
            "gemm_gfx950.hip", "gemm_api.cpp", "probe_gfx950.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # packed-fp32 VALU forms are switched off for all device code
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
+# Per source.  The kernel whose wavefronts own the whole register file (one per SIMD) asks the compiler to keep matrix
+# results where vector instructions can read them (the scores are consumed by the vector pipe); left to its own
+# heuristic it puts every matrix result of such a kernel into accumulation registers and copies the scores out
+# element by element.
+SOURCE_FLAGS = {"attn_fwd_rows64_gfx950.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+NOISE = "is not a recognized feature for this target"
 
 
-def build_lib(extra_flags=(), out: str = LIB, verbose: bool = False) -> str:
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-x", "hip", *srcs, "-o", out]
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    err = "\n".join(l for l in res.stderr.splitlines() if NOISE not in l)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed:\n{' '.join(cmd)}\n{err}")
-    if verbose and err.strip():
-        print(err)
+    return err
+
+
+def build_lib(extra_flags=(), out: str = LIB, verbose: bool = False, jobs: int = 4) -> str:
+    """Every source to an object of its own (with its own flags), then one link."""
+    tmp = tempfile.mkdtemp(prefix="attn_build_")
+    try:
+        def compile_one(src):
+            obj = os.path.join(tmp, src + ".o")
+            cmd = [HIPCC, *FLAGS, *SOURCE_FLAGS.get(src, ()), *extra_flags, "-c", "-x", "hip", os.path.join(CSRC, src), "-o", obj]
+            return obj, _run(cmd)
+
+        with ThreadPoolExecutor(max_workers=jobs) as ex:
+            done = list(ex.map(compile_one, SOURCES))
+        err = "".join(e for _, e in done)
+        err += _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *[o for o, _ in done], "-o", out])
+        if verbose and err.strip():
+            print(err)
+    finally:
+        shutil.rmtree(tmp, ignore_errors=True)
     return out
 
 

@@ -54,10 +54,13 @@ extern "C" const char* attn_status_str(int status) {
 #endif
 namespace {
 const char* const kKernelNames[2][2][3][2] = {ATTN_NAMES_NW(ATTN_NW_FULL_STR), ATTN_NAMES_NW(ATTN_NW_HALF_STR)};
+const char* const kRows64Names[2][2] = {{"attn_fwd_rows64_kernel<0, 128, false>", "attn_fwd_rows64_kernel<0, 128, true>"},
+                                        {"attn_fwd_rows64_kernel<1, 128, false>", "attn_fwd_rows64_kernel<1, 128, true>"}};
 }  // namespace
 
 extern "C" const char* attn_kernel_name(int B, int H, int S, int D, int dtype, int causal) {
     if (B <= 0 || H <= 0 || !attn_supported(S, D, dtype, causal)) return nullptr;
+    if (attn_takes_rows64((long long)B * H, S, D)) return kRows64Names[dtype][causal != 0];
     const int half = attn_pick_nw((long long)B * H, S) == ATTN_NW ? 0 : 1;
     return kKernelNames[half][dtype][D == 32 ? 0 : D == 64 ? 1 : 2][causal != 0];
 }

@@ -47,48 +47,15 @@
 
 #include "attn_launch.h"
 #include "gfx950_common.h"
+#include "attn_device.h"
 
 namespace {
 
 using namespace gfx950;
+using namespace attn_device;
 
 template <int N>
 __device__ __forceinline__ void wait_block_loads() { wait_lds_dma<N>(); }
-
-// plain maxima, without the quiet-NaN canonicalisation the C library semantics would add
-__device__ __forceinline__ float vmax(float a, float b) {
-    float r;
-    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-__device__ __forceinline__ float vmax3(float a, float b, float c) {
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-
-// value held by the other half of the wavefront (lane l <-> lane l^32)
-__device__ __forceinline__ float other_half(float x) {
-    uint32_t u = __builtin_bit_cast(uint32_t, x);
-    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    // lanes <32 get (own, upper's); lanes >=32 get (lower's, own)
-    return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
-}
-
-// XOR swizzle of the 16-byte chunk index inside a K/V row in LDS (row = tile-local key index).
-// D=128 (16 chunks/row, a row spans all 64 banks): 16 consecutive rows must land on 16 different
-//   chunks (b128 reads of K) and 4 consecutive rows x 4 consecutive chunks likewise (transpose
-//   reads of V): swap the two low bit pairs of the row index.
-// D=64 (8 chunks/row, two rows span the banks): the same two conditions with the row parity
-//   already selecting the bank half: bit-reverse bits 1..3 of the row index.
-// D=32 (4 chunks/row, four rows span the banks): row % 4 selects the bank quarter, so the transpose
-//   reads need nothing; for the b128 reads rows r, r+4, r+8, r+12 must differ: bits 2..3 of the row.
-template <int D>
-__device__ __forceinline__ constexpr int swz(int row) {
-    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))
-           : D == 64 ? ((((row >> 1) & 1) << 2) | (((row >> 2) & 1) << 1) | ((row >> 3) & 1))
-                     : ((row >> 2) & 3);
-}
 
 extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
 
@@ -743,6 +710,9 @@ hipError_t launch(const AttnLaunch& a) {
 
 // dispatch on (dtype, D, causal); arguments were validated by the caller
 hipError_t attn_launch(const AttnLaunch& a) {
+    // (a negative scale, folded into the sign of q, stays with the 32-row kernel: this one keeps q where no vector
+    // instruction reaches it)
+    if (attn_takes_rows64(a.BH, a.S, a.D) && a.qsign == 0) return attn_launch_rows64(a);
 #define ATTN_CASE(DT, DD, CZ)                                       \
     if (a.dtype == DT && a.D == DD && (a.causal != 0) == CZ)     \
         return attn_pick_nw(a.BH, a.S) == ATTN_NW ? launch<DT, DD, CZ, ATTN_NW>(a) : launch<DT, DD, CZ, ATTN_NW / 2>(a);

@@ -35,6 +35,13 @@
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif
 
+#ifndef ATTN_ROWS64
+#define ATTN_ROWS64 0  // D = 128, problems that fill the chip: the kernel with 64 query rows per wavefront, one wavefront per SIMD
+#endif
+#ifndef ATTN64_NBUF
+#define ATTN64_NBUF 8  // that kernel's LDS buffers of 32 keys per tensor
+#endif
+
 // Which loop a head dimension runs, the keys per inner-loop block and the LDS buffers per tensor that go with it.
 constexpr bool attn_alternating(int D) { return ATTN_PINGPONG != 0 && (D == 128 || D == 64); }
 constexpr int attn_block_keys(int D) { return attn_alternating(D) ? ATTN_PP_KEYS : ATTN_BC; }
@@ -69,3 +76,9 @@ struct AttnLaunch {
 };
 
 hipError_t attn_launch(const AttnLaunch& a);
+hipError_t attn_launch_rows64(const AttnLaunch& a);   // D = 128 only: 64 query rows per wavefront
+
+// Does this problem take the kernel with 64 query rows per wavefront?  (Workgroups of 256 rows either way.)
+inline bool attn_takes_rows64(long long BH, int S, int D) {
+    return ATTN_ROWS64 != 0 && D == 128 && attn_pick_nw(BH, S) == ATTN_NW;
+}

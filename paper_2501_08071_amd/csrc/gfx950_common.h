@@ -50,6 +50,32 @@ template <> struct Elem<1> {  // bfloat16
     static __device__ __forceinline__ float widen(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
 };
 
+// The same matrix instruction with its accumulator pinned to vector registers and its second operand to
+// accumulation registers, for kernels whose wavefronts own the whole register file: there the compiler puts
+// every matrix result into accumulation registers, which vector instructions cannot read, and a product that
+// the vector pipe consumes (attention scores) would have to be copied out element by element.  Written as asm,
+// so the compiler knows nothing of the instruction's latency: the CALLER keeps every vector read of `d` at
+// least two matrix instructions behind the write (the kernels here keep sixteen).
+template <int DT>
+__device__ __forceinline__ void mfma_vacc_first(f32x16& d, u32x4 a, u32x4 b) {   // d = a.b
+    if constexpr (DT == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+}
+template <int DT>
+__device__ __forceinline__ void mfma_vacc(f32x16& d, u32x4 a, u32x4 b) {         // d += a.b
+    if constexpr (DT == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+
+// 16 bytes per lane from global memory straight into accumulation registers (a resident matrix operand that no vector
+// instruction ever touches: an ordinary value would live in vector registers and be copied over before every use).
+// The compiler does not know of the load: the CALLER waits (vmcnt) before the first use.
+__device__ __forceinline__ u32x4 global_load_acc16(const void* p) {
+    u32x4 r;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(r) : "v"(p) : "memory");
+    return r;
+}
+
 // 4 x 16-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
 // the 8 bytes addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4 of its group.
 __device__ __forceinline__ u32x2 lds_read_tr16(uint32_t addr) {
