@@ -265,8 +265,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     };
 
     if constexpr (PP) {
-        // first operands of the next matrix phase, read before its barrier
-        constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // all of them K operands
+        // first operands of the next matrix phase, read in the vector phase before it (the matrix phase is the one
+        // short of issue slots: every operand read moved out of it shortens it)
+        constexpr int FETCH = ATTN_PP_FETCH < NSUB * KSTEPS ? ATTN_PP_FETCH : NSUB * KSTEPS;   // all of them K operands
         u32x4 pre[FETCH];
         int wary = 0;    // blocks still to go whose row maxima are taken before the weights (wavefront-uniform)
         f32x16 s[NSUB];  // S(k): written by M(k), read by V(k)
@@ -385,7 +386,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
             }
             l_run += psum;
 #pragma unroll
-            for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u] + KB1 * BLKB);
+            for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u % KSTEPS] + KB1 * BLKB + (u / KSTEPS) * 32 * ROWB);
         };
 
 #pragma unroll
@@ -396,7 +397,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
         wait_block_loads<(KAHEAD + VAHEAD - 1) * IPW>();
         __syncthreads();
 #pragma unroll
-        for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u]);
+        for (int u = 0; u < FETCH; ++u) pre[u] = lds_read_b128(kaddr[u % KSTEPS] + (u / KSTEPS) * 32 * ROWB);
         if (grp1) asm volatile("s_barrier" ::: "memory");   // the second group starts half a block late
 
         // In the order of issue K(j) is load number 2 j (K(0) number 1) and V(j) number 2 j + 3 (times IPW

@@ -27,10 +27,6 @@
 #include "gfx950_common.h"
 #include "attn_device.h"
 
-#ifndef ATTN64_ASM_SCORES
-#define ATTN64_ASM_SCORES 0
-#endif
-
 namespace {
 
 using namespace gfx950;
@@ -174,6 +170,8 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
         for (int i = 0; i < DB; ++i)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc_o[r][i][e] = 0.f;
+    static_assert(DB == 4, "mfma_settle takes the four accumulator blocks of a sub-tile");
+    auto settle = [&](int r) __attribute__((always_inline)) { mfma_settle(acc_o[r][0], acc_o[r][1], acc_o[r][2], acc_o[r][3]); };
     float m_run[RS], l_run[RS], m_ref[RS];   // reference maximum (base-2 units) of what is accumulated, this lane's share of the row sum, reference of the block in hand
 #pragma unroll
     for (int r = 0; r < RS; ++r) { m_run[r] = -INFINITY; l_run[r] = 0.f; m_ref[r] = -INFINITY; }
@@ -203,8 +201,10 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
         return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
     auto rescale_o = [&](int r, float alpha) __attribute__((always_inline)) {
-        // the accumulators live in accumulation registers: one block of 16 at a time comes over, is scaled and goes back,
-        // so that this rare path does not claim vector registers the loop needs
+        // the accumulators live in accumulation registers (mfma_aacc): the last matrix instruction on them has to have
+        // finished; then one block of 16 at a time comes over, is scaled and goes back, so that this rare path does
+        // not claim vector registers the loop needs
+        settle(r);
 #pragma unroll
         for (int i = 0; i < DB; ++i) {
             __builtin_amdgcn_sched_barrier(0);
@@ -213,15 +213,18 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // O^T += V(j)^T . P(j)^T of one sub-tile, plain order (a sub-tile's last block)
+    // O^T += V(j)^T . P(j)^T of one sub-tile, plain order (a sub-tile's last block).  Called under a condition, so the
+    // compiler may move the accumulators afterwards: their matrix instructions are waited out first.
     auto pv_plain = [&](int r, const u32x4 (&pf)[2], int VB) __attribute__((always_inline)) {
 #pragma unroll
         for (int tt = 0; tt < NT; ++tt)
 #pragma unroll
             for (int i = 0; i < DB; ++i) {
-                acc_o[r][i] = E::mfma(fetch_v(VB, tt, i), pf[tt], acc_o[r][i]);
+                mfma_aacc<DT>(acc_o[r][i], fetch_v(VB, tt, i), pf[tt]);
                 __builtin_amdgcn_sched_barrier(0);
             }
+        settle(r);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     constexpr int FETCH = ATTN_FETCH < KSTEPS ? ATTN_FETCH : KSTEPS;   // units between an operand's LDS read and its use
@@ -305,47 +308,63 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
             if constexpr (U < KSTEPS) opnd[U] = lds_read_b128(kaddr[U] + KB * BLKB);
             else opnd[U] = fetch_v(VB, (U - KSTEPS) / DB, (U - KSTEPS) % DB);
         };
-        auto weight = [&](int r, int e) __attribute__((always_inline)) {
+        // The vector work of weight e of sub-tile r in two halves, so that a matrix instruction can stand between an
+        // exponential and the first use of its result: the argument and the exponential; then the row sum and, with
+        // every second weight, the rounding of two weights into one register.
+        auto weight_exp = [&](int r, int e) __attribute__((always_inline)) {
             p[r][e] = __builtin_amdgcn_exp2f(fmaf(s_cur[r][e], c, neg_m[r]));
+            asm volatile("" : "+v"(p[r][e]));   // here, in this group, not where the compiler would sink it to
+        };
+        auto weight_sum = [&](int r, int e) __attribute__((always_inline)) {
             if (e % 2 == 1) {
                 uint32_t w = E::pack2(p[r][e - 1], p[r][e]);
-                asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
+                asm volatile("" : "+v"(w));
                 pf_cur[r][e / 8][(e % 8) / 2] = w;
                 if (DT == 0) psum[r] = E::dot2_ones(w, psum[r]);
             }
             // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits, which would
             // cost the logsumexp its accuracy: sum the fp32 values
-            if (DT == 1) {
-                psum[r] += p[r][e];
-                asm volatile("" : "+v"(psum[r]));
+            if (DT == 1) psum[r] += p[r][e];
+            asm volatile("" : "+v"(psum[r]));
+        };
+        // With one wavefront per SIMD nothing else fills the issue slots while a matrix instruction waits for the
+        // pipe: two matrix instructions in a row cost the wavefront a whole matrix instruction's time.  So the unit
+        // is written as four groups that nothing crosses: matrix instruction of the first sub-tile | arguments and
+        // exponentials of both sub-tiles | matrix instruction of the second sub-tile | sums and roundings, the
+        // operand read of a later unit, a block load.  Each vector group fits the matrix instruction before it.
+        auto matrix = [&](auto unit, int r) __attribute__((always_inline)) {
+            constexpr int U = decltype(unit)::value;
+            if constexpr (U < KSTEPS) {
+                if constexpr (U == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) s_nxt[r][e] = 0.f;
+                }
+                s_nxt[r] = E::mfma(opnd[U], qf[r][U], s_nxt[r]);
+            } else {
+                constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
+                mfma_aacc<DT>(acc_o[r][i], opnd[U], pf_prv[r][tt]);
             }
         };
         auto unit_step = [&](auto unit) __attribute__((always_inline)) {
             constexpr int U = decltype(unit)::value;
+            constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
+            if constexpr (R0 == 0) {
+                matrix(unit, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int e = lo; e < hi; ++e)
+#pragma unroll
+                for (int r = R0; r < RS; ++r) weight_exp(r, e);
+            __builtin_amdgcn_sched_barrier(0);
+            matrix(unit, 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = lo; e < hi; ++e)
+#pragma unroll
+                for (int r = R0; r < RS; ++r) weight_sum(r, e);
             if constexpr (U + FETCH < NU) fetch(std::integral_constant<int, U + FETCH>{});
             else pre[U + FETCH - NU] = lds_read_b128(kaddr[U + FETCH - NU] + KB2 * BLKB);
-#pragma unroll
-            for (int r = R0; r < RS; ++r) {
-                if constexpr (U < KSTEPS) {
-#if ATTN64_ASM_SCORES
-                    // the scores stay in vector registers (the vector pipe reads them a whole step later)
-                    if constexpr (U == 0) mfma_vacc_first<DT>(s_nxt[r], opnd[U], qf[r][U]);
-                    else mfma_vacc<DT>(s_nxt[r], opnd[U], qf[r][U]);
-#else
-                    if constexpr (U == 0) {
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) s_nxt[r][e] = 0.f;
-                    }
-                    s_nxt[r] = E::mfma(opnd[U], qf[r][U], s_nxt[r]);
-#endif
-                } else {
-                    constexpr int tt = (U - KSTEPS) / DB, i = (U - KSTEPS) % DB;
-                    acc_o[r][i] = E::mfma(opnd[U], pf_prv[r][tt], acc_o[r][i]);
-                }
-                constexpr int lo = (16 * U) / NU, hi = (16 * (U + 1)) / NU;
-#pragma unroll
-                for (int e = lo; e < hi; ++e) weight(r, e);
-            }
             // the 2 IPW load instructions of this step, evenly spread
             constexpr int NP = 2 * IPW, GAP = NU / NP;
             if constexpr (U % GAP == GAP / 2 && U / GAP < NP) {
@@ -376,6 +395,9 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
             }
             l_run[r] += psum[r];
         }
+        // The steps of sub-tile B alone are reached by run-time conditions, behind which the compiler may move the
+        // accumulators: their matrix instructions are waited out before the step is left.
+        if constexpr (R0 == 1) settle(1);
     };
     // A step in which this wavefront has nothing left to compute: it keeps the barrier, closes a sub-tile that
     // finished with the previous block, and issues its share of the block loads.
@@ -407,24 +429,14 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
             const u32x4 kop = lds_read_b128(kaddr[ks]);
 #pragma unroll
             for (int r = 0; r < RS; ++r) {
-#if ATTN64_ASM_SCORES
-                if (ks == 0) mfma_vacc_first<DT>(s_a[r], kop, qf[r][ks]);
-                else mfma_vacc<DT>(s_a[r], kop, qf[r][ks]);
-#else
                 if (ks == 0) {
 #pragma unroll
                     for (int e = 0; e < 16; ++e) s_a[r][e] = 0.f;
                 }
                 s_a[r] = E::mfma(kop, qf[r][ks], s_a[r]);
-#endif
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-#if ATTN64_ASM_SCORES
-        // the compiler does not know these matrix instructions' latency: wait them out before the vector pipe reads S(0)
-        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-#endif
 #pragma unroll
         for (int r = 0; r < RS; ++r) {
             float mx = s_a[r][0];
@@ -450,8 +462,12 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
         }(std::make_integer_sequence<int, NBUF>{});
     }
     // Under the causal mask sub-tile A is done first: the remaining blocks of the workgroup are steps of sub-tile B
-    // alone, then idle ones; these few steps are not unrolled (the phase is a run-time value).
+    // alone, then idle ones; these few steps are not unrolled (the phase is a run-time value).  Where the compiler
+    // moves accumulators between the two loops or between these steps, their matrix instructions have finished.
     if constexpr (CAUSAL) {
+        settle(0);
+        settle(1);
+        __builtin_amdgcn_sched_barrier(0);
         for (int kb = last_both + 1; kb <= last_max; ++kb) {
             const int ph = kb & (NBUF - 1);
             if (kb <= last[1]) {
@@ -474,6 +490,9 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
             else pv_plain(r, pf_a[r], last_max & (NBUF - 1));
         }
 
+    settle(0);   // the accumulators' last matrix instructions, of which the compiler knows nothing
+    settle(1);
+    __builtin_amdgcn_sched_barrier(0);
     // ---- epilogue: O = acc / l, lse = ln 2 * (m + log2 l), one sub-tile after the other ----
     uint8_t* xp = smem64 + 2 * NBUF * BLKB + wave * 4096;
 #pragma unroll

@@ -31,6 +31,9 @@
 #ifndef ATTN_FETCH
 #define ATTN_FETCH 4  // units between the LDS read of an operand and the matrix instruction that uses it
 #endif
+#ifndef ATTN_PP_FETCH
+#define ATTN_PP_FETCH 4  // alternating-phase loop: K operands of the next matrix phase read ahead, in the vector phase
+#endif
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif

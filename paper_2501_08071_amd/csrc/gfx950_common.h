@@ -50,21 +50,27 @@ template <> struct Elem<1> {  // bfloat16
     static __device__ __forceinline__ float widen(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
 };
 
-// The same matrix instruction with its accumulator pinned to vector registers and its second operand to
-// accumulation registers, for kernels whose wavefronts own the whole register file: there the compiler puts
-// every matrix result into accumulation registers, which vector instructions cannot read, and a product that
-// the vector pipe consumes (attention scores) would have to be copied out element by element.  Written as asm,
-// so the compiler knows nothing of the instruction's latency: the CALLER keeps every vector read of `d` at
-// least two matrix instructions behind the write (the kernels here keep sixteen).
+// The same matrix instruction with its accumulator pinned to accumulation registers, for kernels whose wavefronts own
+// the whole register file and are compiled with matrix results in vector registers by default (so that the vector pipe
+// can read the products it consumes): a long-lived accumulator that no vector instruction touches in the loop goes
+// here and leaves the vector registers to the rest.  Written as asm, so the compiler knows nothing of the
+// instruction's latency: the CALLER passes the accumulator through mfma_settle before anything but another such
+// instruction on the same accumulator reads it.
 template <int DT>
-__device__ __forceinline__ void mfma_vacc_first(f32x16& d, u32x4 a, u32x4 b) {   // d = a.b
-    if constexpr (DT == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+__device__ __forceinline__ void mfma_aacc(f32x16& d, u32x4 a, u32x4 b) {   // d += a.b
+    if constexpr (DT == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
 }
-template <int DT>
-__device__ __forceinline__ void mfma_vacc(f32x16& d, u32x4 a, u32x4 b) {         // d += a.b
-    if constexpr (DT == 0) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+// 24 wait states, after which the results of earlier mfma_aacc on the accumulators passed here are in place.  The
+// accumulators go through the statement, so that no read of them (the compiler's own copies included: they follow
+// the data flow, not the order of asm statements) can be placed ahead of the wait.
+// (The wait comes first and by itself: a copy the compiler makes to bring an accumulator to the second statement
+// then stands behind the wait.)
+__device__ __forceinline__ void mfma_settle(f32x16& a0, f32x16& a1, f32x16& a2, f32x16& a3) {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" : "+a"(a0), "+a"(a1), "+a"(a2), "+a"(a3));
 }
 
 // 16 bytes per lane from global memory straight into accumulation registers (a resident matrix operand that no vector
