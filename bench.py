@@ -41,7 +41,32 @@ ATTN_FILES = ("attn_fwd_gfx950.hip", "attn_fwd_rows64_gfx950.hip", "attn_launch.
 ROW_FILES = ("rowops_gfx950.hip", "rowops_launch.h")
 GEMM_FILES = ("gemm_gfx950.hip", "gemm_launch.h", "gfx950_common.h")
 TRAFFIC = {
-    # attention (filled in from the counter runs; see the profile named in "source")
+    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 150253 * 2.0, "write_kib": 132096 * 1.0, "files": ATTN_FILES,
+                                      "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+                                      "source": "profiles/attn_fwd_kernel_S4096_D128_bf16_causal.md"},
+    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 895330 * 2.0, "write_kib": 264192 * 1.0, "files": ATTN_FILES,
+                                       "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+                                       "source": "profiles/attn_fwd_kernel_all_workloads.md"},
+    "B16_H16_S2048_D64_f16_peaky": {"fetch_kib": 98509.4 * 2.0, "write_kib": 133120 * 1.0, "files": ATTN_FILES,
+                                    "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+                                    "source": "profiles/attn_fwd_kernel_S2048_D64_f16.md"},
+    "B4_H16_S1024_D64_f16": {"fetch_kib": 12469.8 * 2.0, "write_kib": 16640 * 1.0, "files": ATTN_FILES,
+                             "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+                             "source": "profiles/attn_fwd_kernel_S2048_D64_f16.md"},
+    # the row kernels (workload name as rowop_run reports it)
+    "softmax_512x4096_f16 x16 rows": {"fetch_kib": 32802.5 * 2.0, "write_kib": 65536.0 * 1.0, "files": ROW_FILES,
+                                      "kernel_sha256": "efc90703c88cd78fc96c429b78ffe9d0151fd5461670fbd9a3e86f4f176ea240",
+                                      "source": "profiles/rowop_reg_kernel_softmax_rmsnorm.md"},
+    "rmsnorm_1x32x4096x64_f16 x16 rows": {"fetch_kib": 131108.0 * 2.0, "write_kib": 262144.0 * 1.0, "files": ROW_FILES,
+                                          "kernel_sha256": "efc90703c88cd78fc96c429b78ffe9d0151fd5461670fbd9a3e86f4f176ea240",
+                                          "source": "profiles/rowop_reg_kernel_softmax_rmsnorm.md"},
+    # the GEMM + LeakyReLU kernels (the paper's shape; the 256 x 256 tile's launches)
+    "mmLeakyReLu_1x512x512x2048_f16": {"fetch_kib": 10272.5 * 2.0, "write_kib": 512.0 * 1.0, "files": GEMM_FILES,
+                                       "kernel_sha256": "4621da25a85d63d48a6b552e285a1a26e4d75c798cc8b9d9c8efe85953557683",
+                                       "source": "profiles/gemm_lrelu_kernel_mmLeakyReLu.md"},
+    "mmLeakyReLu_1x4096x4096x4096_f16": {"fetch_kib": 147536.0 * 2.0, "write_kib": 32768.0 * 1.0, "files": GEMM_FILES,
+                                         "kernel_sha256": "4621da25a85d63d48a6b552e285a1a26e4d75c798cc8b9d9c8efe85953557683",
+                                         "source": "profiles/gemm_lrelu_kernel_mmLeakyReLu.md"},
 }
 
 

@@ -66,8 +66,8 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                      uint32_t qsign, int o16) {
     using E = Elem<DT>;
     constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
-    // keys per block: 32, or 64 in the alternating-phase loop (a phase then has twice the work between its
-    // two barriers; half as many buffers of twice the size)
+    // keys per block: 32, or 64 (D = 128) and 128 (D = 64) in the alternating-phase loop (a phase then has more work
+    // between its two barriers; half as many buffers, each larger)
     constexpr int BC = attn_block_keys(D);
     constexpr int NSUB = BC / 32;      // 32-key sub-blocks (one accumulator tile of S each)
     constexpr int NBUF = attn_buffers(D);   // LDS buffers per tensor (a power of two); block k lives in buffer k % NBUF
@@ -91,7 +91,7 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     constexpr int IPT = BC / RPI;      // such instructions per block and tensor
     constexpr int IPW = IPT >= NW ? IPT / NW : 1;   // ... per loading wavefront
     constexpr int LOADERS = IPT / IPW;              // wavefronts that issue loads
-    static_assert((BC == 32 || (PP && BC == 64)) && IPT % IPW == 0 && LOADERS <= NW, "load split");
+    static_assert((BC == 32 || (PP && (BC == 64 || (BC == 128 && D == 64)))) && IPT % IPW == 0 && LOADERS <= NW, "load split");
     // LDS: K buffers 0..NBUF-1 | V buffers 0..NBUF-1
 
     const float c = c_arg;

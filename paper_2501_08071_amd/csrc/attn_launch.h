@@ -7,7 +7,10 @@
 #define ATTN_NW 8   // wavefronts per workgroup, each owning 32 query rows
 #endif
 #ifndef ATTN_PP_KEYS
-#define ATTN_PP_KEYS 64   // keys per inner-loop block in the alternating-phase loop (32 or 64)
+#define ATTN_PP_KEYS 64   // keys per inner-loop block in the alternating-phase loop at D = 128 (32 or 64)
+#endif
+#ifndef ATTN_PP_KEYS_D64
+#define ATTN_PP_KEYS_D64 (2 * ATTN_PP_KEYS)   // the same at D = 64 (32, 64 or 128), where a key costs half the matrix work and half the LDS: twice the keys per phase
 #endif
 #define ATTN_BC 32  // keys per inner-loop block in the interleaved loop
 #ifndef ATTN_MAX_SLACK
@@ -47,10 +50,11 @@
 
 // Which loop a head dimension runs, the keys per inner-loop block and the LDS buffers per tensor that go with it.
 constexpr bool attn_alternating(int D) { return ATTN_PINGPONG != 0 && (D == 128 || D == 64); }
-constexpr int attn_block_keys(int D) { return attn_alternating(D) ? ATTN_PP_KEYS : ATTN_BC; }
-constexpr int attn_buffers(int D) { return attn_block_keys(D) == 64 ? ATTN_NBUF / 2 : ATTN_NBUF; }   // blocks of 64 keys: half as many (128 KiB at D = 128, 64 KiB at D = 64)
+constexpr int attn_block_keys(int D) { return attn_alternating(D) ? (D == 64 ? ATTN_PP_KEYS_D64 : ATTN_PP_KEYS) : ATTN_BC; }
+constexpr int attn_buffers(int D) { return attn_block_keys(D) * D > 32 * 128 ? ATTN_NBUF / 2 : ATTN_NBUF; }   // blocks of more than 8 KiB: half as many (128 KiB in all with the shipped blocks, D = 128 and 64)
 
 static_assert(ATTN_PP_KEYS == 32 || ATTN_PP_KEYS == 64, "block size of the alternating-phase loop");
+static_assert(ATTN_PP_KEYS_D64 == 32 || ATTN_PP_KEYS_D64 == 64 || ATTN_PP_KEYS_D64 == 128, "block size of the alternating-phase loop at D = 64");
 
 // Wavefronts per workgroup for a problem of BH (b,h) pairs and S rows: ATTN_NW (256 query rows per workgroup),
 // or half of that when the larger tiles would leave at least half of the 256 compute units without a

@@ -17,6 +17,8 @@ random inputs, Section 4.1).
   python -m paper_2501_08071_amd.tune build            compile every state of the grid (CPU, no GPU needed)
   python -m paper_2501_08071_amd.tune play [-w 3]      play the game on the GPU, print the trajectory,
                                                        store the result in tune_cache.json
+  python -m paper_2501_08071_amd.tune time [-w 3] shipped rows64 ...
+                                                       check and time single states (what a profiler run wraps)
 
 The game logic (`play_game`) is independent of the GPU: it takes a function state -> seconds.
 """
@@ -39,7 +41,7 @@ KNOBS: Dict[str, Tuple[str, Tuple[int, ...]]] = {
     "barrier_every": ("ATTN_BARRIER_EVERY", (1, 2)),  # interleaved loop: key blocks per workgroup barrier
     "fetch": ("ATTN_FETCH", (2, 4, 6)),             # matrix instructions between an LDS operand read and its use
     "nbuf": ("ATTN_NBUF", (4, 8)),                  # LDS buffers per tensor = how far ahead blocks are requested
-    "block": ("ATTN_PP_KEYS", (32, 64)),            # alternating phases: keys per block = work between two barriers
+    "block": ("ATTN_PP_KEYS", (32, 64)),            # alternating phases: keys per block at D = 128 (twice as many at D = 64) = work between two barriers
     "prefetch": ("ATTN_PP_FETCH", (4, 8)),          # alternating phases: K operands of the next matrix phase read in the vector phase
     "rows64": ("ATTN_ROWS64", (0, 1)),              # D = 128: 64 query rows per wavefront, one wavefront per SIMD
 }
@@ -208,6 +210,10 @@ def main(argv=None) -> int:
     p = sub.add_parser("play")
     p.add_argument("-w", "--workload", type=int, default=3)
     p.add_argument("--warmup", type=int, default=100); p.add_argument("--steps", type=int, default=100)
+    t = sub.add_parser("time", help="check and time single schedules (the unit a profiler run wraps)")
+    t.add_argument("-w", "--workload", type=int, default=3)
+    t.add_argument("--warmup", type=int, default=100); t.add_argument("--steps", type=int, default=100)
+    t.add_argument("states", nargs="+", help="state names as `build` prints them, or `shipped` / `start` / `rows64`")
     args = ap.parse_args(argv)
     if args.cmd == "build":
         build_grid(jobs=args.jobs)
@@ -215,9 +221,20 @@ def main(argv=None) -> int:
     import torch
     from . import inputs as I
     if not torch.cuda.is_available():
-        print("tune play: no GPU visible", file=sys.stderr)
+        print(f"tune {args.cmd}: no GPU visible", file=sys.stderr)
         return 1
     w = I.workload(args.workload)
+    if args.cmd == "time":
+        named = {"shipped": SHIPPED, "start": START, "rows64": SHIPPED[:-1] + (1,)}
+        named.update({state_name(s): s for s in all_states()})
+        measure = gpu_measure(args.workload, args.warmup, args.steps)
+        for name in args.states:
+            if name not in named:
+                print(f"tune time: no such state: {name}", file=sys.stderr)
+                return 2
+            sec = measure(named[name])
+            print(f"{w.name}  {state_name(named[name]):60s} {sec*1e3:8.4f} ms  {w.flops/sec/1e12:7.1f} TFLOP/s", flush=True)
+        return 0
     res = play_game(gpu_measure(args.workload, args.warmup, args.steps))
     flops = w.flops
     print(f"workload {w.name} on {torch.cuda.get_device_name(0)}")

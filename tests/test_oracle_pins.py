@@ -335,7 +335,6 @@ def test_hand_worked_rational_weights(causal, dtype):
     q, k, v = (bits(np.array(rows[n], np.float32)[None, None], dtype) for n in "qkv")
     scale = math.log(2.0)
     o, lse = oracle.attn_oracle(q, k, v, causal, scale, dtype)
-    # the oracle takes scale as fp32: ln 2 rounded to fp32 is off by 1.5e-8 relative, logits are <= 3
     for i, (num, den) in want["causal" if causal else "noncausal"].items():
-        assert np.abs(o[0, 0, i] - np.array(num) / den).max() < 1e-6
-        assert abs(lse[0, 0, i] - math.log(den)) < 1e-6
+        assert np.abs(o[0, 0, i] - np.array(num) / den).max() < 1e-12
+        assert abs(lse[0, 0, i] - math.log(den)) < 1e-12
