@@ -41,17 +41,17 @@ ATTN_FILES = ("attn_fwd_gfx950.hip", "attn_fwd_rows64_gfx950.hip", "attn_launch.
 ROW_FILES = ("rowops_gfx950.hip", "rowops_launch.h")
 GEMM_FILES = ("gemm_gfx950.hip", "gemm_launch.h", "gfx950_common.h")
 TRAFFIC = {
-    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 150253 * 2.0, "write_kib": 132096 * 1.0, "files": ATTN_FILES,
-                                      "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+    "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 154304 * 2.0, "write_kib": 132096 * 1.0, "files": ATTN_FILES,
+                                      "kernel_sha256": "6dc62b7782281d4f9acfaec650059587ab1b85fd9b2540fb3a35955c5401ba1f",
                                       "source": "profiles/attn_fwd_kernel_S4096_D128_bf16_causal.md"},
-    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 895330 * 2.0, "write_kib": 264192 * 1.0, "files": ATTN_FILES,
-                                       "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+    "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 925857 * 2.0, "write_kib": 264192 * 1.0, "files": ATTN_FILES,
+                                       "kernel_sha256": "6dc62b7782281d4f9acfaec650059587ab1b85fd9b2540fb3a35955c5401ba1f",
                                        "source": "profiles/attn_fwd_kernel_all_workloads.md"},
-    "B16_H16_S2048_D64_f16_peaky": {"fetch_kib": 98509.4 * 2.0, "write_kib": 133120 * 1.0, "files": ATTN_FILES,
-                                    "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+    "B16_H16_S2048_D64_f16_peaky": {"fetch_kib": 98512.3 * 2.0, "write_kib": 133120 * 1.0, "files": ATTN_FILES,
+                                    "kernel_sha256": "6dc62b7782281d4f9acfaec650059587ab1b85fd9b2540fb3a35955c5401ba1f",
                                     "source": "profiles/attn_fwd_kernel_S2048_D64_f16.md"},
-    "B4_H16_S1024_D64_f16": {"fetch_kib": 12469.8 * 2.0, "write_kib": 16640 * 1.0, "files": ATTN_FILES,
-                             "kernel_sha256": "dc26a096e5310bfbef008972c6141b617e4b583f7a77a2d237340a6dc46d185a",
+    "B4_H16_S1024_D64_f16": {"fetch_kib": 12471.7 * 2.0, "write_kib": 16640 * 1.0, "files": ATTN_FILES,
+                             "kernel_sha256": "6dc62b7782281d4f9acfaec650059587ab1b85fd9b2540fb3a35955c5401ba1f",
                              "source": "profiles/attn_fwd_kernel_S2048_D64_f16.md"},
     # the row kernels (workload name as rowop_run reports it)
     "softmax_512x4096_f16 x16 rows": {"fetch_kib": 32802.5 * 2.0, "write_kib": 65536.0 * 1.0, "files": ROW_FILES,
@@ -186,6 +186,8 @@ def attn_bounds(P, w, probes):
                  conversion) at the rate the vector pipes sustain when they do nothing else (measured in this run)
     l2           the K and V bytes the workgroups stream from L2 into LDS (every workgroup its own copy of the
                  keys it sees) at the L2 read bandwidth measured in this run
+    issue_port   the vector work of the softmax plus what the matrix instructions take from the issue of the other
+                 wavefront on their SIMD (two wavefronts per SIMD, one port), at 2.4 GHz
     launch_floor what a kernel that does nothing costs per launch, back to back"""
     rows = P.attn_launch_rows(w.B, w.H, w.S, w.D, w.dtype, w.causal)
     nqt = (w.S + rows - 1) // rows
@@ -199,6 +201,11 @@ def attn_bounds(P, w, probes):
            "hbm_ms": attn_algorithmic_bytes(w) / (PEAK_HBM_GBS * 1e9) * 1e3,
            "scores": scores, "l2_to_lds_bytes": l2_bytes}
     if probes:
+        # one issue port per SIMD for vector and matrix instructions (1024 SIMDs at the nominal 2.4 GHz): the vector work
+        # of 64 scores and what a matrix instruction takes from the wavefront next to it, both measured in this run
+        t = "bf16" if w.dtype_name == "bf16" else "f16"
+        cycles = scores / 64.0 * probes["issue"][f"valu_cycles_per_64_scores_{t}"] + w.flops / 32768.0 * probes["issue"]["mfma_issue_cycles"]
+        out["issue_port_ms"] = cycles / (1024 * 2.4e9) * 1e3
         out["softmax_valu_ms"] = scores / probes["softmax_valu_scores_per_s"] * 1e3
         out["l2_ms"] = l2_bytes / probes["l2_read_bytes_per_s"] * 1e3
         out["launch_floor_us"] = probes["launch_floor_us"]
@@ -211,7 +218,8 @@ def run_probes(P, dtype):
             "softmax_valu_scores_per_s": P.probe_softmax_valu(full=True),
             "exp2_fma_per_s": P.probe_softmax_valu(full=False),
             "l2_read_bytes_per_s": P.probe_l2_read(),
-            "launch_floor_us": P.probe_launch_floor_us()}
+            "launch_floor_us": P.probe_launch_floor_us(),
+            "issue": P.probe_issue_share()}
 
 
 def cpu_baseline(w, q, k, v, budget_s=15.0):

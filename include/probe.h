@@ -39,6 +39,20 @@ long long probe_softmax_valu(float *out, int workgroups, int iters, int full, vo
  */
 long long probe_l2_read(const void *buf, float *out, int region_kib, int workgroups, int iters, void *stream);
 
+/*
+ * What a matrix instruction takes from the instruction issue of the other wavefront on its SIMD.  `workgroups`
+ * workgroups of eight wavefronts, two per SIMD, one workgroup per compute unit (96 KiB of LDS each).  On every
+ * SIMD one wavefront does the softmax's vector work of `iters` x 32 scores per lane -- vector_mode 1: multiply-add,
+ * exp2, row-sum addition, half a conversion to bfloat16; 2: multiply-add, exp2, half a conversion to binary16, half
+ * a two-way dot product; 0: it exits at once -- and, if matrix_on != 0, the other issues 32x32x16 bfloat16 matrix
+ * instructions until its partner is done (vector_mode 0: `iters` x 32 of them).  matrix_on == 0 needs
+ * vector_mode != 0.
+ * out: workgroups * 8 pairs of 64-bit integers, written: for wavefront w of workgroup b, out[2 (8 b + w)] = shader
+ * clock cycles its loop took, out[2 (8 b + w) + 1] = iterations of 32 (matrix instructions for w < 4, scores per lane
+ * for w >= 4) it made.  Returns 0.
+ */
+int probe_issue_share(long long *out, int workgroups, int iters, int matrix_on, int vector_mode, void *stream);
+
 /* A kernel that does nothing, `workgroups` x `threads`: the cost of a launch by itself.  Returns 0. */
 int probe_empty(int workgroups, int threads, void *stream);
 

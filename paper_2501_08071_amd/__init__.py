@@ -14,7 +14,7 @@ __all__ = ["inputs", "attn_fwd", "attn_fwd_o16", "attn_supported", "attn_status_
 
 def __getattr__(name):
     if name in ("attn_fwd", "attn_fwd_raw", "attn_fwd_o16", "attn_fwd_o16_raw", "attn_supported", "attn_status_str", "attn_kernel_name",
-                "attn_tile_rows", "attn_tile_keys", "attn_launch_rows", "probe_mfma", "probe_softmax_valu", "probe_l2_read", "probe_launch_floor_us", "lib", "AttnError", "F16", "BF16",
+                "attn_tile_rows", "attn_tile_keys", "attn_launch_rows", "probe_mfma", "probe_softmax_valu", "probe_l2_read", "probe_launch_floor_us", "probe_issue_share", "lib", "AttnError", "F16", "BF16",
                 "softmax_rows_fwd", "softmax_rows_fwd_raw", "rmsnorm_fwd", "rmsnorm_fwd_raw", "rowops_path", "rowops_status_str",
                 "RowopsError", "gemm_leakyrelu_fwd", "gemm_leakyrelu_fwd_raw", "gemm_path", "gemm_status_str", "GemmError"):
         from . import binding

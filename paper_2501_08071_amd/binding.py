@@ -57,6 +57,8 @@ def _load() -> ctypes.CDLL:
     lib.probe_l2_read.restype = ctypes.c_longlong
     lib.probe_empty.argtypes = [ctypes.c_int, ctypes.c_int, vp]
     lib.probe_empty.restype = ctypes.c_int
+    lib.probe_issue_share.argtypes = [vp] + [ctypes.c_int] * 4 + [vp]
+    lib.probe_issue_share.restype = ctypes.c_int
     # include/rowops.h
     lib.softmax_rows_fwd.argtypes = [vp, vp, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, vp]
     lib.softmax_rows_fwd.restype = ctypes.c_int
@@ -158,6 +160,47 @@ def probe_launch_floor_us(workgroups: int = 256, threads: int = 256, launches: i
     e1.record(st)
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) * 1e3 / launches
+
+
+def probe_issue_share(iters: int = 400, workgroups: int = 256) -> dict:
+    """What the two wavefronts of a SIMD cost each other, in shader-clock cycles (medians over all wavefronts):
+    mfma_cycles_alone                       per 32x32x16 matrix instruction, its wavefront alone on the SIMD
+    valu_cycles_per_64_scores_{bf16,f16}    the softmax's vector work of one score in each of the 64 lanes (the
+                                            bfloat16 kernel's mix, or the binary16 one with its dot instructions),
+                                            the wavefront alone on the SIMD
+    ..._next_to_mfma                        the same while the other wavefront streams matrix instructions
+    mfma_cycles_next_to_{bf16,f16}          per matrix instruction of that other wavefront meanwhile
+    mfma_issue_cycles                       what one matrix instruction adds to the time of a vector wavefront without
+                                            dot instructions (the bfloat16 mix)"""
+    out = torch.zeros(workgroups * 16, dtype=torch.int64, device="cuda")
+    st = torch.cuda.current_stream()
+
+    def run(matrix_on, vmode):
+        for _ in range(2):   # the second launch counts
+            if lib.probe_issue_share(out.data_ptr(), workgroups, iters, matrix_on, vmode, st.cuda_stream) != 0:
+                raise RuntimeError("probe_issue_share: bad argument or refused launch")
+        torch.cuda.synchronize()
+        r = out.cpu().reshape(workgroups, 8, 2).to(torch.float64)
+        return r[:, :4].reshape(-1, 2), r[:, 4:].reshape(-1, 2)     # matrix wavefronts, vector wavefronts: (cycles, iterations)
+
+    def med(t):
+        return float(t.median())
+
+    res = {}
+    m, _ = run(1, 0)
+    res["mfma_cycles_alone"] = med(m[:, 0] / (32.0 * m[:, 1]))
+    for vmode, name in ((1, "bf16"), (2, "f16")):
+        _, v0 = run(0, vmode)
+        alone = med(v0[:, 0] / (32.0 * v0[:, 1]))
+        m, v = run(1, vmode)
+        together = med(v[:, 0] / (32.0 * v[:, 1]))
+        mfma_per_cycle = med(32.0 * m[:, 1] / m[:, 0])
+        res[f"valu_cycles_per_64_scores_{name}"] = alone
+        res[f"valu_cycles_per_64_scores_{name}_next_to_mfma"] = together
+        res[f"mfma_cycles_next_to_{name}"] = 1.0 / mfma_per_cycle
+        if vmode == 1:
+            res["mfma_issue_cycles"] = (together - alone) / (together * mfma_per_cycle)
+    return res
 
 
 def attn_fwd_raw(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, causal, scale, dtype, stream) -> int:

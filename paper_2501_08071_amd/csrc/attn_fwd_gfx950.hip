@@ -65,6 +65,11 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                      void* __restrict__ o, float* __restrict__ lse, int S, int BH, int nqt, float c_arg,
                      uint32_t qsign, int o16) {
     using E = Elem<DT>;
+    // Row sum of the weights.  By one fp32 addition per weight, or -- binary16 at D = 64 -- from the rounded weights, two
+    // per dot instruction.  A dot instruction issued while the other wavefront of the SIMD streams matrix instructions
+    // waits for a gap in that stream (measured: include/probe.h, probe_issue_share), so it only pays where the vector
+    // phase outlasts the other wavefront's matrix phase and the dot instructions can stand at its end: D = 64.
+    constexpr bool SUM_DOT = ATTN_F16_SUM_DOT != 0 && DT == 0 && D == 64;
     constexpr int BR = NW * 32;        // query rows per workgroup, 32 per wavefront
     // keys per block: 32, or 64 (D = 128) and 128 (D = 64) in the alternating-phase loop (a phase then has more work
     // between its two barriers; half as many buffers, each larger)
@@ -345,15 +350,17 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         p[r] = __builtin_amdgcn_exp2f(fmaf(s[sub][r], c, nm));
-                        if (r % 2 == 1) {
-                            const uint32_t w = E::pack2(p[r - 1], p[r]);
-                            pf[2 * sub + r / 8][(r % 8) / 2] = w;
-                            // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
-                            // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
-                            if (DT == 0) psum = E::dot2_ones(w, psum);
-                        }
-                        if (DT == 1) psum += p[r];
+                        if (r % 2 == 1) pf[2 * sub + r / 8][(r % 8) / 2] = E::pack2(p[r - 1], p[r]);
+                        // bfloat16 keeps only 8 bits, which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
+                        if (!SUM_DOT) psum += p[r];
                     }
+                }
+                if constexpr (SUM_DOT) {
+                    __builtin_amdgcn_sched_barrier(0);   // the dot instructions last, when the other wavefront's matrix phase is over
+#pragma unroll
+                    for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) psum = E::dot2_ones(pf[tt][e], psum);
                 }
             };
             constexpr int WARY = ATTN_WARY;
@@ -521,11 +528,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     uint32_t w = E::pack2(p[r - 1], p[r]);
                     asm volatile("" : "+v"(w));   // round here, under the matrix instruction, not later
                     pf_cur[r / 8][(r % 8) / 2] = w;
-                    if (DT == 0) psum = E::dot2_ones(w, psum);
+                    if (SUM_DOT) psum = E::dot2_ones(w, psum);
                 }
-                // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits,
-                // which would cost the logsumexp its 1e-3 accuracy: sum the fp32 values
-                if (DT == 1) {
+                if (!SUM_DOT) {
                     psum += p[r];
                     asm volatile("" : "+v"(psum));   // add here, under the matrix instruction, not later
                 }
@@ -583,9 +588,9 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
                     if (r % 2 == 1) {
                         const uint32_t w = E::pack2(p[r - 1], p[r]);
                         pf_cur[r / 8][(r % 8) / 2] = w;
-                        if (DT == 0) psum = E::dot2_ones(w, psum);
+                        if (SUM_DOT) psum = E::dot2_ones(w, psum);
                     }
-                    if (DT == 1) psum += p[r];
+                    if (!SUM_DOT) psum += p[r];
                 }
             }
             // block k is done: its weights were taken against m_ref; everything older against m_run

@@ -256,9 +256,8 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
             if (e % 2 == 1) {
                 const uint32_t w = E::pack2(p[e - 1], p[e]);
                 pf_cur[e / 8][(e % 8) / 2] = w;
-                if (DT == 0) psum = E::dot2_ones(w, psum);
             }
-            if (DT == 1) psum += p[e];
+            psum += p[e];   // the fp32 weights, both types (a dot instruction would wait on the matrix pipe)
         }
     };
 
@@ -320,11 +319,8 @@ void attn_fwd_rows64_kernel(const uint16_t* __restrict__ q, const uint16_t* __re
                 uint32_t w = E::pack2(p[r][e - 1], p[r][e]);
                 asm volatile("" : "+v"(w));
                 pf_cur[r][e / 8][(e % 8) / 2] = w;
-                if (DT == 0) psum[r] = E::dot2_ones(w, psum[r]);
             }
-            // binary16: rounded weights summed two per dot instruction; bfloat16 keeps only 8 bits, which would
-            // cost the logsumexp its accuracy: sum the fp32 values
-            if (DT == 1) psum[r] += p[r][e];
+            psum[r] += p[r][e];   // row sum from the fp32 weights, both types
             asm volatile("" : "+v"(psum[r]));
         };
         // With one wavefront per SIMD nothing else fills the issue slots while a matrix instruction waits for the

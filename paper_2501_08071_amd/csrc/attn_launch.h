@@ -37,6 +37,9 @@
 #ifndef ATTN_PP_FETCH
 #define ATTN_PP_FETCH 4  // alternating-phase loop: K operands of the next matrix phase read ahead, in the vector phase
 #endif
+#ifndef ATTN_F16_SUM_DOT
+#define ATTN_F16_SUM_DOT 1  // binary16 at D = 64: row sums from the rounded weights, two per v_dot2c_f32_f16, at the end of the vector phase (0: from the fp32 weights, one addition each, as everywhere else)
+#endif
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif

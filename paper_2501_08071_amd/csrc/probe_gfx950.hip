@@ -6,10 +6,15 @@
 //                  optionally the row-sum addition and the conversion to 16 bit
 //   probe_l2_read  every workgroup reads a region small enough to stay in its XCD's L2, over and over
 //   probe_empty    a kernel that does nothing: what a launch costs by itself
+//   probe_issue_share  two wavefronts per SIMD, one issuing matrix instructions only, the other the softmax's vector
+//                  work only: what a matrix instruction takes from the issue of the wavefront next to it
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/probe.h"
+#include "gfx950_common.h"
 
 namespace {
 
@@ -89,8 +94,8 @@ __global__ __launch_bounds__(256) void softmax_valu_probe_kernel(float* out, int
                 if (j % 2 == 1) {
                     f32x2 two = {x[j - 1], x[j]};
                     uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
-                    asm volatile("" : "+v"(w));   // the conversion is kept although nothing reads most of them
-                    packed ^= w;
+                    asm volatile("" : "+v"(w));   // the conversion is kept although nothing reads its result
+                    packed = w;
                 }
             }
         }
@@ -125,6 +130,90 @@ __global__ __launch_bounds__(256) void l2_read_probe_kernel(const u32x4* __restr
 }
 
 __global__ void empty_probe_kernel() {}
+
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+
+// Eight wavefronts, two per SIMD (wavefront w and w + 4 share one; the dynamic LDS keeps a second workgroup off the
+// compute unit).  Wavefronts 0-3 issue nothing but matrix instructions, four accumulators in turn, until their partner
+// has finished (or, with the partners idle, `iters` times 32); wavefronts 4-7 do the vector work of `iters` x 32 scores
+// per lane: VMODE 1 the bfloat16 kernel's (multiply-add, exp2, addition, half a conversion), VMODE 2 the binary16
+// kernel's (multiply-add, exp2, half a conversion, half a two-way dot product for the row sum).  Every wavefront
+// writes the shader-clock cycles of its loop and the iterations it made.
+template <int VMODE>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void issue_share_probe_kernel(long long* out, int iters, int matrix_on, int max_iters, float c, float d) {
+    extern __shared__ __attribute__((aligned(16))) uint32_t done[];   // done[w]: wavefront w + 4 has finished
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (threadIdx.x < 4) done[threadIdx.x] = 0u;
+    __syncthreads();
+    long long t0 = 0, t1 = 0;
+    int made = 0;
+    float keep = 0.f;
+    if (wave < 4) {
+        if (matrix_on) {
+            const u32x4 a = {0x3f803f80u, 0x3f813f80u, 0x3f803f82u, 0x3f803f80u};
+            f32x16 acc[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+            volatile LDS_AS uint32_t* flag = (volatile LDS_AS uint32_t*)done + wave;
+            const int limit = VMODE ? max_iters : iters;
+            t0 = __builtin_amdgcn_s_memtime();
+            for (; made < limit; ++made) {
+                if (VMODE && __builtin_amdgcn_readfirstlane(*flag) != 0u) break;   // one LDS read per 32 matrix instructions
+#pragma unroll
+                for (int u = 0; u < 32; ++u)
+                    acc[u % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, a), acc[u % 4], 0, 0, 0);
+            }
+            t1 = __builtin_amdgcn_s_memtime();
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) keep += acc[j][r];
+        }
+    } else {
+        if (VMODE) {
+            float x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = 0.001f * (float)((threadIdx.x * 8 + j) & 1023);
+            float sum = 0.f;
+            uint32_t packed = 0u;
+            t0 = __builtin_amdgcn_s_memtime();
+            for (; made < iters; ++made) {
+#pragma unroll
+                for (int u = 0; u < 32; ++u) {
+                    float& y = x[u & 7];
+                    y = __builtin_amdgcn_exp2f(fmaf(y, c, d));
+                    if (VMODE == 1) sum += y;
+                    if (u & 1) {
+                        const f32x2 two = {x[(u - 1) & 7], y};
+                        uint32_t w;
+                        if (VMODE == 1) w = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, bf16x2));
+                        else {
+                            w = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
+                            sum = gfx950::Elem<0>::dot2_ones(w, sum);
+                        }
+                        asm volatile("" : "+v"(w));   // the conversion is kept although nothing reads its result
+                        packed = w;
+                    }
+                    asm volatile("" : "+v"(y));
+                }
+            }
+            t1 = __builtin_amdgcn_s_memtime();
+            keep = sum + __builtin_bit_cast(float, packed & 0x3fffffffu);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) keep += x[j];
+            if (lane == 0) done[wave - 4] = 1u;
+        }
+    }
+    asm volatile("" :: "v"(keep));
+    if (lane == 0) {
+        out[((size_t)blockIdx.x * 8 + wave) * 2] = t1 - t0;
+        out[((size_t)blockIdx.x * 8 + wave) * 2 + 1] = made;
+    }
+}
 
 }  // namespace
 
@@ -167,4 +256,20 @@ extern "C" int probe_empty(int workgroups, int threads, void* stream) {
     void* args[] = {nullptr};
     return hipLaunchKernel(reinterpret_cast<const void*>(&empty_probe_kernel), dim3((unsigned)workgroups), dim3((unsigned)threads),
                            args, 0, (hipStream_t)stream) == hipSuccess ? 0 : -1;
+}
+
+extern "C" int probe_issue_share(long long* out, int workgroups, int iters, int matrix_on, int vector_mode, void* stream) {
+    if (out == nullptr || workgroups <= 0 || workgroups > 65536 || iters <= 0 || iters > (1 << 20)) return -1;
+    if (vector_mode < 0 || vector_mode > 2 || (!matrix_on && vector_mode == 0)) return -1;
+    if ((reinterpret_cast<uintptr_t>(out) & 7u) != 0) return -1;
+    int it = iters, mon = matrix_on != 0, max_it = iters * 8;   // a partner's 32 scores take less than 8 x 32 matrix instructions
+    float c = 0.5f, d = -1.0f;
+    void* args[] = {&out, &it, &mon, &max_it, &c, &d};
+    const void* fn = vector_mode == 0 ? reinterpret_cast<const void*>(&issue_share_probe_kernel<0>)
+                   : vector_mode == 1 ? reinterpret_cast<const void*>(&issue_share_probe_kernel<1>)
+                                      : reinterpret_cast<const void*>(&issue_share_probe_kernel<2>);
+    constexpr unsigned lds_bytes = 96u * 1024u;   // more than half of a compute unit's: one workgroup each
+    static std::atomic<uint64_t> told[3];
+    if (gfx950::announce_lds(fn, lds_bytes, told[vector_mode]) != hipSuccess) return -1;
+    return hipLaunchKernel(fn, dim3((unsigned)workgroups), dim3(512), args, lds_bytes, (hipStream_t)stream) == hipSuccess ? 0 : -1;
 }

@@ -44,7 +44,7 @@ def test_every_declared_symbol_is_exported(P):
         assert hasattr(P.lib, n), f"{n} is declared in gemm.h but not exported"
     text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "probe.h")).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(probe_[a-z0-9_]+)\s*\(", text)))
-    assert names == ["probe_empty", "probe_l2_read", "probe_mfma", "probe_softmax_valu"]
+    assert names == ["probe_empty", "probe_issue_share", "probe_l2_read", "probe_mfma", "probe_softmax_valu"]
     for n in names:
         assert hasattr(P.lib, n), f"{n} is declared in probe.h but not exported"
     assert not any(n.startswith("probe") or "probe" in n for n in declared_symbols())   # measuring aids stay out of attn.h
@@ -120,6 +120,9 @@ def test_probes_reject_bad_arguments(P):
     assert h(4096 + 4, 4096, 1024, 8, 1, None) == -1 and h(4096, 4096, 1024, 0, 1, None) == -1
     e = P.lib.probe_empty
     assert e(0, 64, None) == -1 and e(1, 0, None) == -1 and e(1, 2048, None) == -1
+    i = P.lib.probe_issue_share
+    assert i(None, 1, 1, 1, 1, None) == -1 and i(4096, 0, 1, 1, 1, None) == -1 and i(4096, 1, 0, 1, 1, None) == -1
+    assert i(4096, 1, 1, 1, 3, None) == -1 and i(4096, 1, 1, 0, 0, None) == -1 and i(4096 + 4, 1, 1, 1, 1, None) == -1
 
 
 def test_status_strings(P):

@@ -275,6 +275,28 @@ def test_workloads_every_element(wid):
     print(f"{w.name} full: max-abs {mx:.2e} mean-abs {mean:.2e} lse-rel {lrel:.2e}")
 
 
+def test_issue_share_probe_runs():
+    """Every wavefront reports its loop: the vector wavefronts make exactly `iters` iterations, the matrix wavefronts
+    stop when their partner is done (or after `iters` when it is idle); all cycle counts positive; the derived figures
+    are in the range the instruction timings allow (a 32x32x16 matrix instruction occupies its pipe for 32 cycles)."""
+    out = torch.zeros(4 * 16, dtype=torch.int64, device="cuda")
+    assert P.lib.probe_issue_share(out.data_ptr(), 4, 50, 1, 1, None) == 0
+    torch.cuda.synchronize()
+    r = out.cpu().reshape(4, 8, 2)
+    assert torch.all(r[:, 4:, 1] == 50) and torch.all(r[:, :4, 1] >= 1) and torch.all(r[:, :4, 1] <= 400) and torch.all(r[..., 0] > 0)
+    assert P.lib.probe_issue_share(out.data_ptr(), 4, 50, 1, 0, None) == 0
+    torch.cuda.synchronize()
+    r = out.cpu().reshape(4, 8, 2)
+    assert torch.all(r[:, :4, 1] == 50) and torch.all(r[:, 4:, 1] == 0)
+    res = P.probe_issue_share(iters=100, workgroups=64)
+    assert 30.0 <= res["mfma_cycles_alone"] <= 40.0
+    assert 0.0 <= res["mfma_issue_cycles"] <= 32.0
+    for t in ("bf16", "f16"):
+        assert 10.0 <= res[f"valu_cycles_per_64_scores_{t}"] <= 40.0
+        assert res[f"valu_cycles_per_64_scores_{t}_next_to_mfma"] >= res[f"valu_cycles_per_64_scores_{t}"] - 1.0
+        assert 30.0 <= res[f"mfma_cycles_next_to_{t}"] <= 64.0
+
+
 def test_matrix_instruction_probe_runs():
     """The measuring aid: returns the flop count of its launch and a finite, positive rate; constant operands
     accumulate exactly (every lane sums iters * 16 instructions * 16 products of 1.0 * 1.0 per accumulator element)."""
