@@ -213,7 +213,7 @@ def main(argv=None) -> int:
     t = sub.add_parser("time", help="check and time single schedules (the unit a profiler run wraps)")
     t.add_argument("-w", "--workload", type=int, default=3)
     t.add_argument("--warmup", type=int, default=100); t.add_argument("--steps", type=int, default=100)
-    t.add_argument("states", nargs="+", help="state names as `build` prints them, or `shipped` / `start` / `rows64`")
+    t.add_argument("states", nargs="+", help="state names as `build` prints them, or `shipped` / `start` / `rows64` / `all`")
     args = ap.parse_args(argv)
     if args.cmd == "build":
         build_grid(jobs=args.jobs)
@@ -228,7 +228,8 @@ def main(argv=None) -> int:
         named = {"shipped": SHIPPED, "start": START, "rows64": SHIPPED[:-1] + (1,)}
         named.update({state_name(s): s for s in all_states()})
         measure = gpu_measure(args.workload, args.warmup, args.steps)
-        for name in args.states:
+        states = [n for name in args.states for n in ([state_name(s) for s in all_states()] if name == "all" else [name])]
+        for name in states:
             if name not in named:
                 print(f"tune time: no such state: {name}", file=sys.stderr)
                 return 2
