@@ -8,11 +8,11 @@ epilogue) on one batch of the synthetic workload, inputs resident in HBM.  Print
 
 Timing follows the paper's protocol (Sections 3.6 and 5.1: warm-up iterations, then timed ones, the mean;
 differences of about 1 % count as noise).  Before the W warm-up steps the harness launches the kernel back
-to back until the launch time has settled: under sustained matrix load the chip's power management first
-boosts the clock, then overshoots downwards for some ten milliseconds and only then holds a steady clock, so
-a short warm-up would time the transient, not the kernel (`settle` in the output says how long it took).
-`--cold` adds a figure with the caches flushed between iterations, each launch under its own event pair, as the
-paper does for its reward signal.
+to back until the launch time has settled: the first launches of a process run up to 20 % slower, for some
+tens of milliseconds, until the chip's clock and power management have found their level under the new load,
+so a short warm-up would time the transient, not the kernel (`settle` in the output says how long it took).
+The full line (and `--cold`) also carries the figure with the caches flushed between launches, each launch
+under its own event pair, five runs, as the paper does for its reward signal (`cold_cache`).
 
 Next to the headline the same line carries short runs of the other workloads (`workloads`), the paper's
 memory-bound pair and its fused GEMM at Table 2's shapes and at one streaming size (`also`), and the
@@ -411,7 +411,7 @@ def main():
     ap.add_argument("--brief", action="store_true",
                     help="the headline workload only: no other workloads, no other kernels, no probes, no oracle timing")
     ap.add_argument("--no-settle", action="store_true", help="skip the settling launches (shows the power transient)")
-    ap.add_argument("--cold", action="store_true", help="also time with caches flushed between launches")
+    ap.add_argument("--cold", action="store_true", help="also time with caches flushed between launches (the full line does anyway; this adds it to --brief)")
     ap.add_argument("--no-probe", action="store_true", help="skip the probes (measured denominators and bounds)")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--data", choices=["synthetic", "zeros"], default="synthetic",
@@ -493,7 +493,7 @@ def main():
         out["roofline"]["probes"] = probes
     out["roofline"]["bounds"] = attn_bounds(P, w, probes)
 
-    if args.cold:
+    if args.cold or (not args.brief and args.data == "synthetic"):
         # the paper's protocol (Sections 3.6, 5.1) with cold caches: every launch under its own event pair, a 1 GiB
         # buffer (more than L2 + Infinity Cache) rewritten before it, outside the pair; mean of `steps` launches,
         # repeated 5 times: mean and standard deviation of the 5 means
