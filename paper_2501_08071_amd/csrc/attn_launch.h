@@ -40,6 +40,12 @@
 #ifndef ATTN_F16_SUM_DOT
 #define ATTN_F16_SUM_DOT 1  // binary16 at D = 64: row sums from the rounded weights, two per v_dot2c_f32_f16, at the end of the vector phase (0: from the fp32 weights, one addition each, as everywhere else)
 #endif
+#ifndef ATTN_PP_PRIO_M
+#define ATTN_PP_PRIO_M 1  // alternating-phase loop: issue priority of a wavefront in its matrix phase ...
+#endif
+#ifndef ATTN_PP_PRIO_V
+#define ATTN_PP_PRIO_V 0  // ... and in its vector phase (0 .. 3; equal: the priority is never touched)
+#endif
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif
