@@ -337,11 +337,16 @@ def blas_threads():
         return os.cpu_count()
 
 
-def gemm_run(P, torch, size, warmup, steps, with_cpu, floor_us=None):
-    """The paper's fused GEMM + LeakyReLU (Table 2: B, M, N, K = 1, 512, 512, 2048, float16), or a square one of
-    `size`.  MFMA roofline: 2 M N K flops per launch."""
+def gemm_run(P, torch, size, warmup, steps, with_cpu, floor_us=None, bmm=False):
+    """The paper's fused GEMM + LeakyReLU (Table 2: B, M, N, K = 1, 512, 512, 2048, float16), a square one of
+    `size`, or (`bmm`) Table 2's batch matrix multiplication, B, M, N, K = 4, 512, 512, 2048: the same kernel with
+    slope 1, which makes the activation the identity.  MFMA roofline: 2 B M N K flops per launch."""
     from paper_2501_08071_amd import inputs as I
-    if size:
+    slope = 1.0 if bmm else 0.01
+    if bmm:
+        name = "bmm_4x512x512x2048_f16"
+        batch, M, N, K, dt = I.GEMM_SHAPES[name]
+    elif size:
         name = f"mmLeakyReLu_1x{size}x{size}x{size}_f16"
         batch, M, N, K, dt = 1, size, size, size, I.F16
     else:
@@ -354,7 +359,7 @@ def gemm_run(P, torch, size, warmup, steps, with_cpu, floor_us=None):
     stream = torch.cuda.current_stream()
 
     def step():
-        P.gemm_leakyrelu_fwd(a, b, 0.01, c=c, stream=stream)
+        P.gemm_leakyrelu_fwd(a, b, slope, c=c, stream=stream)
 
     m = measure(step, stream, torch, warmup, steps)
     flops = 2.0 * batch * M * N * K
@@ -366,7 +371,7 @@ def gemm_run(P, torch, size, warmup, steps, with_cpu, floor_us=None):
         "value": flops * steps / m["wall_s"] / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": m["wall_s"] * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": name, "batch": batch, "M": M, "N": N, "K": K, "slope": 0.01,
+        "config": {"workload": name, "batch": batch, "M": M, "N": N, "K": K, "slope": slope,
                    "path": P.gemm_path(batch, M, N, K, dt)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS["f16"], "unit": "TFLOP/s",
                      "frac": achieved / PEAK_TFLOPS["f16"], "traffic": traffic, "traffic_unit": "bytes/launch",
@@ -379,7 +384,7 @@ def gemm_run(P, torch, size, warmup, steps, with_cpu, floor_us=None):
         from oracle import gemm as G
         mm = min(M, 256)
         t0 = time.perf_counter()
-        G.gemm_leakyrelu(ab[:, :mm], bb, 0.01, dt)
+        G.gemm_leakyrelu(ab[:, :mm], bb, slope, dt)
         dtm = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": 2.0 * batch * mm * N * K / dtm / 1e12, "unit": "TFLOP/s", "cores": blas_threads(),
                                "kind": "oracle", "sample": f"the first {mm} of {M} rows of a, {dtm:.2f} s, fp64 numpy matmul",
@@ -396,7 +401,7 @@ def brief(o):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--op", choices=["attn", "softmax", "rmsnorm", "gemm"], default="attn",
+    ap.add_argument("--op", choices=["attn", "softmax", "rmsnorm", "gemm", "bmm"], default="attn",
                     help="attn: the hot path (default); softmax, rmsnorm, gemm: the paper's memory-bound kernels and its "
                          "fused GEMM + LeakyReLU at Table 2's shapes")
     ap.add_argument("--gemm-size", type=int, default=0, help="gemm: a square problem M = N = K of this size instead of Table 2's")
@@ -433,9 +438,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
-    if args.op == "gemm":
+    if args.op in ("gemm", "bmm"):
         floor = None if args.no_probe else P.probe_launch_floor_us()
-        print(json.dumps(gemm_run(P, torch, args.gemm_size, args.warmup, args.steps, not args.no_cpu, floor)))
+        print(json.dumps(gemm_run(P, torch, args.gemm_size, args.warmup, args.steps, not args.no_cpu, floor, bmm=args.op == "bmm")))
         return
     if args.op != "attn":
         floor = None if args.no_probe else P.probe_launch_floor_us()
@@ -530,6 +535,7 @@ def main():
             "softmax": [brief(rowop_run(P, torch, "softmax", mul, 20, 50, cpu and mul == 1, floor)) for mul in (1, 16)],
             "rmsnorm": [brief(rowop_run(P, torch, "rmsnorm", mul, 20, 50, cpu and mul == 1, floor)) for mul in (1, 16)],
             "gemm": [brief(gemm_run(P, torch, size, 20, 50, cpu and size == 0, floor)) for size in (0, 4096)],
+            "bmm": [brief(gemm_run(P, torch, 0, 20, 50, cpu, floor, bmm=True))],
         }
     out["bench_seconds"] = time.perf_counter() - t_begin
     print(json.dumps(out))

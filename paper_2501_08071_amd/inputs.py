@@ -204,6 +204,7 @@ def gen_rows(n_rows: int, n_cols: int, dtype: int, *, tensor_id: int = 0, seed: 
 
 GEMM_SHAPES = {
     "mmLeakyReLu_1x512x512x2048_f16": (1, 512, 512, 2048, F16),      # B, M, N, K (Table 2)
+    "bmm_4x512x512x2048_f16": (4, 512, 512, 2048, F16),              # Table 2's batch matrix multiplication: the same kernel with slope 1
 }
 
 

@@ -112,6 +112,12 @@ def test_paper_shape_every_element(P):
     run(P, batch, M, N, K, dt, slope=0.01)
 
 
+def test_paper_bmm_shape_every_element(P):
+    """Table 2: bmm, B, M, N, K = 4, 512, 512, 2048, float16: slope 1 makes the activation the identity."""
+    batch, M, N, K, dt = I.GEMM_SHAPES["bmm_4x512x512x2048_f16"]
+    run(P, batch, M, N, K, dt, slope=1.0)
+
+
 @pytest.mark.parametrize("slope", [0.0, 1.0, -0.5, 0.2])
 def test_slopes(P, slope):
     run(P, 1, 96, 80, 64, I.F16, slope=slope)
