@@ -246,11 +246,28 @@ def cpu_baseline(w, q, k, v, budget_s=15.0):
             "seconds": dt}
 
 
-def attn_short_run(P, torch, wid, seed, probes, steps=20):
+def cpu_whole_problem(w, q, k, v):
+    """The oracle on a whole (small) workload: with all host threads and with one."""
+    import oracle
+    out = {}
+    n_all = oracle.num_threads()
+    for key, n in (("all_threads", n_all), ("one_thread", 1)):
+        oracle.set_num_threads(n)
+        t0 = time.perf_counter()
+        oracle.attn_oracle(q, k, v, w.causal, w.scale, w.dtype)
+        dt = time.perf_counter() - t0
+        out[key] = {"value": w.flops / dt / 1e12, "unit": "TFLOP/s", "cores": n, "kind": "oracle", "sample": "the whole workload, fp64",
+                    "seconds": dt}
+    oracle.set_num_threads(n_all)
+    return out
+
+
+def attn_short_run(P, torch, wid, seed, probes, steps=20, with_cpu=False):
     """One of the other workloads, briefly: settle, 5 warm-up and `steps` timed launches."""
     from paper_2501_08071_amd import inputs as I
     w = I.workload(wid)
-    _, dev = attn_device_inputs(w, torch, seed)
+    host, dev = attn_device_inputs(w, torch, seed)
+    cpu = cpu_whole_problem(w, *host) if with_cpu and wid in (1, 2) else None   # the two the oracle finishes in a second or two
     step, stream = attn_step(P, torch, w, dev)
     m = measure(step, stream, torch, 5, steps)
     peak = PEAK_TFLOPS[w.dtype_name]
@@ -260,7 +277,7 @@ def attn_short_run(P, torch, wid, seed, probes, steps=20):
             "kernel": P.attn_kernel_name(w.B, w.H, w.S, w.D, w.dtype, w.causal), "steps": steps,
             "per_launch_ms": m["per_launch_ms"], "settle_launches": m["settle"]["launches"],
             "traffic": traffic, "traffic_source": source, "algorithmic_bytes": attn_algorithmic_bytes(w),
-            "bounds": attn_bounds(P, w, probes)}
+            "bounds": attn_bounds(P, w, probes), "cpu_baseline": cpu}
 
 
 # ---- the paper's memory-bound pair ------------------------------------------------------------------
@@ -527,7 +544,7 @@ def main():
         del dev, step
         torch.cuda.empty_cache()
         # the other workloads, briefly (1, 2, 4, 5 and the paper's own attention shape, workload 6), whichever is not the headline
-        out["workloads"] = [attn_short_run(P, torch, wid, seed, probes) for wid in (1, 2, 4, 5, 6) if wid != args.workload]
+        out["workloads"] = [attn_short_run(P, torch, wid, seed, probes, with_cpu=not args.no_cpu) for wid in (1, 2, 4, 5, 6) if wid != args.workload]
         # the paper's other kernels: Table 2's shapes, and one size that streams from HBM
         floor = probes["launch_floor_us"] if probes else None
         cpu = not args.no_cpu
