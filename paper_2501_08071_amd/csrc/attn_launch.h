@@ -14,13 +14,13 @@
 #endif
 #define ATTN_BC 32  // keys per inner-loop block in the interleaved loop
 #ifndef ATTN_MAX_SLACK
-#define ATTN_MAX_SLACK 15.0f  // log2 of the largest sum of 16 softmax weights tolerated before the reference maximum is moved
+#define ATTN_MAX_SLACK 15.0f  // log2 of the largest sum of a lane's softmax weights of one block tolerated before the reference maximum is moved
 #endif
 #ifndef ATTN_WARY
 #define ATTN_WARY 16  // alternating-phase loop: after a reference maximum moved, blocks whose row maxima are taken before the weights
 #endif
 #ifndef ATTN_NBUF
-#define ATTN_NBUF 8   // LDS buffers of 32 keys per tensor (power of two): 8 x 2 x 8 KiB = 128 KiB at D = 128, one workgroup per CU
+#define ATTN_NBUF 8   // LDS buffers per tensor for blocks of up to 8 KiB (a power of two); larger blocks get half as many: 4 x 2 x 16 KiB = 128 KiB with the shipped blocks at D = 128 and 64, one workgroup per CU
 #endif
 #ifndef ATTN_BARRIER_EVERY
 #define ATTN_BARRIER_EVERY 2  // key blocks per workgroup barrier (1 or 2)
@@ -67,7 +67,7 @@ static_assert(ATTN_PP_KEYS_D64 == 32 || ATTN_PP_KEYS_D64 == 64 || ATTN_PP_KEYS_D
 
 // Wavefronts per workgroup for a problem of BH (b,h) pairs and S rows: ATTN_NW (256 query rows per workgroup),
 // or half of that when the larger tiles would leave at least half of the 256 compute units without a
-// workgroup (the smaller workgroups also fit two to a compute unit at D <= 64).
+// workgroup (the smaller workgroups also fit two to a compute unit at D = 32).
 #ifndef ATTN_SMALL_TILES
 #define ATTN_SMALL_TILES 128
 #endif
