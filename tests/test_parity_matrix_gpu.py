@@ -74,8 +74,9 @@ def test_random_shapes_scales_and_ranges():
 def test_non_finite_v_row_above_the_diagonal(bad):
     """The header asks for finite q, k and v everywhere: masked keys enter the second product with weight 0, and 0 * Inf
     is not a number.  This pins what that means.  A non-finite row j of v: the rows of O that see key j are non-finite
-    in the oracle too; of the rows that do not, those in earlier key blocks (64 keys) come out exactly as without the
-    bad row; the rows of j's own block before j are the ones the requirement is there for (they are not checked)."""
+    in the oracle too; of the rows that do not, those in earlier key blocks come out exactly as without the
+    bad row (`attn_tile_keys` keys per block); the rows of j's own block before j are the ones the requirement is there
+    for (they are not checked)."""
     B, H, S, D, dtype, j = 1, 2, 200, 64, F16, 150
     q, k, v = I.gen_tensors(B, H, S, D, dtype, workload_id=77)
     dq, dk, dv = (to_device(t, dtype) for t in (q, k, v))
@@ -84,7 +85,8 @@ def test_non_finite_v_row_above_the_diagonal(bad):
     dv_bad[:, :, j, :] = bad
     o, lse = P.attn_fwd(dq, dk, dv_bad, True, 0.125)
     torch.cuda.synchronize()
-    first_of_block = (j // 64) * 64
+    keys = P.attn_tile_keys(D, dtype, True)
+    first_of_block = (j // keys) * keys
     assert torch.equal(o[:, :, :first_of_block], o_clean[:, :, :first_of_block])       # earlier blocks: untouched, bit for bit
     assert torch.equal(lse, lse_clean)                                                   # v takes no part in the logsumexp
     v_bad = v.copy()
