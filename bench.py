@@ -42,16 +42,16 @@ ROW_FILES = ("rowops_gfx950.hip", "rowops_launch.h")
 GEMM_FILES = ("gemm_gfx950.hip", "gemm_launch.h", "gfx950_common.h")
 TRAFFIC = {
     "B2_H32_S4096_D128_bf16_causal": {"fetch_kib": 147418 * 2.0, "write_kib": 132096 * 1.0, "files": ATTN_FILES,
-                                      "kernel_sha256": "487d0fce0b770afc912faeddfebad9f97e8e99620bc53f20e36e742c8c2dbc99",
+                                      "kernel_sha256": "90cf59d9fbf8f596177c62da2977753833bbabfe9f23af8e242831a8f3448e93",
                                       "source": "profiles/attn_fwd_kernel_S4096_D128_bf16_causal.md"},
     "B1_H32_S16384_D128_bf16_causal": {"fetch_kib": 920443 * 2.0, "write_kib": 264192 * 1.0, "files": ATTN_FILES,
-                                       "kernel_sha256": "487d0fce0b770afc912faeddfebad9f97e8e99620bc53f20e36e742c8c2dbc99",
+                                       "kernel_sha256": "90cf59d9fbf8f596177c62da2977753833bbabfe9f23af8e242831a8f3448e93",
                                        "source": "profiles/attn_fwd_kernel_all_workloads.md"},
     "B16_H16_S2048_D64_f16_peaky": {"fetch_kib": 98509.6 * 2.0, "write_kib": 133120 * 1.0, "files": ATTN_FILES,
-                                    "kernel_sha256": "487d0fce0b770afc912faeddfebad9f97e8e99620bc53f20e36e742c8c2dbc99",
+                                    "kernel_sha256": "90cf59d9fbf8f596177c62da2977753833bbabfe9f23af8e242831a8f3448e93",
                                     "source": "profiles/attn_fwd_kernel_S2048_D64_f16.md"},
     "B4_H16_S1024_D64_f16": {"fetch_kib": 12472.7 * 2.0, "write_kib": 16640 * 1.0, "files": ATTN_FILES,
-                             "kernel_sha256": "487d0fce0b770afc912faeddfebad9f97e8e99620bc53f20e36e742c8c2dbc99",
+                             "kernel_sha256": "90cf59d9fbf8f596177c62da2977753833bbabfe9f23af8e242831a8f3448e93",
                              "source": "profiles/attn_fwd_kernel_S2048_D64_f16.md"},
     # the row kernels (workload name as rowop_run reports it)
     "softmax_512x4096_f16 x16 rows": {"fetch_kib": 32802.5 * 2.0, "write_kib": 65536.0 * 1.0, "files": ROW_FILES,

@@ -176,6 +176,13 @@ void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict_
     // same number of loads and the code has no branch; the address arithmetic is scalar.
     auto issue_piece = [&](int which, int blk, int i, uint32_t dst) {
         if (LOADERS < NW && wave >= LOADERS) return;
+        if constexpr (ATTN_DEBUG_POISON != 0) {
+            // Debug build: what this load is about to overwrite is first filled with NaN patterns.  A wavefront that
+            // still reads the buffer -- a load issued a barrier too early -- then shows in the output instead of quietly
+            // reading the old block or the new one.
+            *(LDS_AS u32x4*)(uintptr_t)(lds_wave + dst + lane * 16) = u32x4{0x7fff7fffu, 0x7fff7fffu, 0x7fff7fffu, 0x7fff7fffu};
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
         const int b = blk < nblk - 1 ? blk : nblk - 1;
         const uint16_t* src = (which ? vh : kh) + (size_t)b * (BC * D);
         lds_dma16(lds_wave + dst, src, b >= nfull ? goff_r[i] : goff[i]);

@@ -46,6 +46,9 @@
 #ifndef ATTN_PP_PRIO_V
 #define ATTN_PP_PRIO_V 0  // ... and in its vector phase (0 .. 3; equal: the priority is never touched)
 #endif
+#ifndef ATTN_DEBUG_POISON
+#define ATTN_DEBUG_POISON 0  // debug build: an LDS buffer is filled with NaN patterns right before the load that overwrites it
+#endif
 #ifndef ATTN_WPE
 #define ATTN_WPE 2  // wavefronts per SIMD the register budget is sized for
 #endif

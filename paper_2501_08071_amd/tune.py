@@ -127,18 +127,28 @@ def variant_path(s: State) -> str:
     return os.path.join(VARIANTS, f"libattn_{state_name(s)}.so")
 
 
+# The shipped schedule once more as a debug build: every LDS buffer is filled with NaN patterns right before the load
+# that overwrites it, so that a read that comes after its buffer was given away shows in the output (a race detector
+# for the load pipeline; tests/test_tune_gpu.py runs it against the oracle).
+POISON_LIB = os.path.join(VARIANTS, "libattn_debug_poison.so")
+
+
 def build_grid(states: Sequence[State] = None, jobs: int = 4) -> None:
     from concurrent.futures import ThreadPoolExecutor
     from . import build as B
     os.makedirs(VARIANTS, exist_ok=True)
+    with_poison = states is None
     states = list(states or all_states())
 
     def one(s):
+        if s is None:
+            B.build_lib(extra_flags=["-DATTN_DEBUG_POISON=1"], out=POISON_LIB)
+            return "debug_poison"
         B.build_lib(extra_flags=state_flags(s), out=variant_path(s))
         return state_name(s)
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        for name in ex.map(one, states):
+        for name in ex.map(one, ([None] if with_poison else []) + states):
             print("built", name, flush=True)
 
 
