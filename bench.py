@@ -172,6 +172,7 @@ def attn_step(P, torch, w, dev):
 
     def step():
         P.attn_fwd(dq, dk, dv, w.causal, w.scale, o=o, lse=lse, stream=stream)
+    step.outputs = (o, lse)
     return step, stream
 
 
@@ -222,8 +223,9 @@ def run_probes(P, dtype):
             "issue": P.probe_issue_share()}
 
 
-def cpu_baseline(w, q, k, v, budget_s=15.0):
-    """The fp64 oracle as it stands, timed on the host cores over a bounded row sample of the workload."""
+def cpu_baseline(w, q, k, v, budget_s=15.0, got=None):
+    """The fp64 oracle as it stands, timed on the host cores over a bounded row sample of the workload.  With `got`
+    (the o and lse tensors the timed launches wrote) the sampled rows are also compared: `parity`."""
     import oracle
 
     def pairs(rows):
@@ -238,12 +240,21 @@ def cpu_baseline(w, q, k, v, budget_s=15.0):
     n = int(min(w.S, max(len(probe), budget_s * rate / (pairs(np.arange(w.S)) / w.S))))
     rows = np.sort(rng.choice(w.S, n, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.attn_oracle(q, k, v, w.causal, w.scale, w.dtype, rows=rows)
+    o_ref, l_ref = oracle.attn_oracle(q, k, v, w.causal, w.scale, w.dtype, rows=rows)
     dt = time.perf_counter() - t0
     flops = 4.0 * w.D * pairs(rows)
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{n} of {w.S} query rows (seeded random) of every (b,h), {dt:.1f} s, fp64",
-            "seconds": dt}
+    out = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+           "sample": f"{n} of {w.S} query rows (seeded random) of every (b,h), {dt:.1f} s, fp64",
+           "seconds": dt}
+    if got is not None:
+        # the timed configuration's own output against the oracle, on the sampled rows (the bar of the test-suite)
+        o, lse = got
+        idx = rows.astype(np.int64)
+        d = np.abs(o[:, :, idx].cpu().numpy().astype(np.float64) - o_ref)
+        dl = np.abs(lse[:, :, idx].cpu().numpy().astype(np.float64) - l_ref) / np.maximum(1.0, np.abs(l_ref))
+        out["parity"] = {"rows": int(n), "max_abs": float(d.max()), "mean_abs": float(d.mean()), "lse_rel": float(dl.max()),
+                         "within_bar": bool(d.max() <= 2e-2 and d.mean() <= 2e-3 and dl.max() <= 1e-3)}
+    return out
 
 
 def cpu_whole_problem(w, q, k, v):
@@ -538,7 +549,7 @@ def main():
         del flush
 
     if not args.no_cpu and args.data == "synthetic":
-        out["cpu_baseline"] = cpu_baseline(w, q, k, v)
+        out["cpu_baseline"] = cpu_baseline(w, q, k, v, got=step.outputs)
 
     if not args.brief and args.data == "synthetic":
         del dev, step
